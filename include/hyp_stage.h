@@ -1,0 +1,172 @@
+/*
+ * hyp_stage.h - C ABI of the stage-forward library for AMD MI355X (gfx950).
+ *
+ * A *stage* is the unit of work that the paper's pipeline hands to one node: the
+ * contiguous range of decoder blocks I_j(p) = { i : p_{j-1} < i <= p_j } (Eq. 6),
+ * executed in strict order (Eq. 1) on the activation tensor
+ * batch x sequence x hidden that travels between tiers (Sec. IV-A).  Every block
+ * is the one of Sec. III-A / Fig. 2: RMS Norm -> grouped-query attention with
+ * rotary position encoding -> residual, RMS Norm -> SwiGLU feed-forward ->
+ * residual.  Requests are first *prefilled* (the whole prompt) and then *decoded*
+ * one token per step against the keys and values cached at prefill (the
+ * experiments of Sec. V-A use 64 prompt tokens and 128 or 256 generated ones,
+ * with weights and caches resident while generating, Sec. V-D).
+ *
+ * Conventions the paper leaves open and this library fixes (the CPU oracle used
+ * by the tests fixes the same ones):
+ *   - pre-norm residuals around both sub-layers; eps is added to the mean square
+ *     inside the square root; there are no biases;
+ *   - RoPE pairs element i with i + head_dim/2 of every query and key head
+ *     (rotate-half) and turns the pair by pos * rope_base^(-2i/head_dim);
+ *   - query head h reads KV head h / (n_q_heads / n_kv_heads);
+ *   - scores are scaled by 1/sqrt(head_dim); a query at position p sees keys at
+ *     positions 0..p and nothing else;
+ *   - prefill token t of a request sits at position t; a decode token sits at
+ *     the position equal to the number of tokens already cached;
+ *   - [l_start, l_end) is the 0-based half-open form of the paper's 1-based
+ *     (p_{j-1}, p_j].
+ *
+ * All pointers are plain addresses.  "device" = memory of the current HIP device
+ * that the caller owns (e.g. a PyTorch tensor's storage) and keeps alive for the
+ * time stated; "host" = ordinary process memory.  No call allocates or frees
+ * device memory: the caller supplies one workspace.  No call throws, aborts or
+ * prints; every failure is a status code plus a message from stage_last_error().
+ * A stage is not thread-safe; use one stage per host thread or lock outside.
+ */
+#ifndef HYP_STAGE_H
+#define HYP_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HYP_API __attribute__((visibility("default")))
+
+typedef struct hyp_stage hyp_stage_t; /* opaque */
+
+typedef enum {
+  HYP_OK = 0,
+  HYP_EINVAL = 1,    /* null pointer, bad layer range, bad enum                  */
+  HYP_ESHAPE = 2,    /* shape the block definition does not admit                */
+  HYP_ECAPACITY = 3, /* batch / sequence / token count beyond what was configured */
+  HYP_ESTATE = 4,    /* call out of order (decode before prefill, ...)           */
+  HYP_EDEVICE = 5,   /* a HIP call failed; text in stage_last_error()            */
+  HYP_ENOMEM = 6     /* workspace too small / host allocation failed             */
+} hyp_status_t;
+
+typedef enum { HYP_F32 = 0, HYP_BF16 = 1 } hyp_dtype_t;
+
+/* hyp_stage_config_t.flags */
+#define HYP_FLAG_PLAIN_KERNELS 1u /* diagnostics: run the shape-generic HIP kernels even \
+                                     where the MFMA kernels apply                        */
+
+typedef struct {
+  int32_t hidden;       /* H                                                  */
+  int32_t n_q_heads;    /* query heads                                        */
+  int32_t n_kv_heads;   /* key/value heads; must divide n_q_heads             */
+  int32_t head_dim;     /* d, even                                            */
+  int32_t ffn_dim;      /* SwiGLU inner width I                               */
+  float rms_eps;
+  float rope_base;
+  int32_t dtype;        /* hyp_dtype_t: type of weights, activations and cache */
+  int32_t max_batch;    /* requests resident at once                          */
+  int32_t max_seq;      /* per-request capacity: prompt + generated tokens    */
+  int64_t max_prefill_tokens; /* bound on sum(seq_lens) of one stage_prefill   */
+  uint32_t flags;
+  uint32_t reserved;    /* must be 0                                          */
+} hyp_stage_config_t;
+
+/* Weights of one block: device pointers, row-major [out_features, in_features]
+ * (y = x W^T), type = config dtype.  Read during stage_create only. */
+typedef struct {
+  const void *attn_norm_g; /* [hidden]                       */
+  const void *wq;          /* [n_q_heads*head_dim, hidden]   */
+  const void *wk;          /* [n_kv_heads*head_dim, hidden]  */
+  const void *wv;          /* [n_kv_heads*head_dim, hidden]  */
+  const void *wo;          /* [hidden, n_q_heads*head_dim]   */
+  const void *ffn_norm_g;  /* [hidden]                       */
+  const void *w_gate;      /* [ffn_dim, hidden]              */
+  const void *w_up;        /* [ffn_dim, hidden]              */
+  const void *w_down;      /* [hidden, ffn_dim]              */
+} hyp_layer_weights_t;
+
+/* Bytes of device workspace stage_create needs for this configuration and layer
+ * range (weights in the library's own layout, KV cache, position tables,
+ * scratch).  Returns 0 if the arguments are invalid. */
+HYP_API size_t stage_workspace_bytes(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end);
+
+/* Build the stage that owns blocks [l_start, l_end) (Eq. 6).
+ *   layers     host array of l_end - l_start weight records (device pointers
+ *              inside); record i belongs to block l_start + i.
+ *   workspace  device, >= stage_workspace_bytes(), 256-byte aligned, owned by the
+ *              caller and kept alive and untouched until stage_destroy.
+ *   hip_stream a hipStream_t (0 = the null stream), borrowed; every later call on
+ *              this stage enqueues its work there.
+ * The weights are copied into the workspace in the library's layout and the
+ * call returns only after that copy has finished, so the caller may release the
+ * original weight tensors afterwards.
+ * Errors: HYP_EINVAL (null pointer, l_start < 0, l_start >= l_end, bad dtype,
+ * reserved != 0), HYP_ESHAPE (non-positive size, n_q_heads % n_kv_heads != 0, odd
+ * head_dim), HYP_ENOMEM (workspace too small or misaligned), HYP_EDEVICE. */
+HYP_API hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end,
+                          const hyp_layer_weights_t *layers, void *workspace,
+                          size_t workspace_bytes, void *hip_stream, hyp_stage_t **out);
+
+/* Prefill: run the stage's blocks over the prompts of `batch` requests and fill
+ * their KV cache (Sec. III-A block, Eq. 1 order; the input is the activation
+ * tensor of Sec. IV-A, i.e. hidden states, also for the first stage).
+ *   hidden_in  device, [sum(seq_lens), hidden] row-major, requests packed one
+ *              after the other without padding; read-only.
+ *   seq_lens   host, [batch], each in 1..max_seq; read before the call returns.
+ *   hidden_out device, same shape and type; may be the same buffer as hidden_in.
+ * Any earlier requests of the stage are dropped: request b of this call
+ * becomes slot b.  The work is enqueued on the stage's stream; the call does not
+ * wait for it.
+ * Errors: HYP_EINVAL (null), HYP_ECAPACITY (batch < 1 or > max_batch, a length
+ * outside 1..max_seq, sum > max_prefill_tokens), HYP_EDEVICE.  On error the
+ * stage keeps its previous requests. */
+HYP_API hyp_status_t stage_prefill(hyp_stage_t *stage, const void *hidden_in, const int32_t *seq_lens,
+                           int32_t batch, void *hidden_out);
+
+/* One decode step: one new token for every resident request, at the position
+ * equal to its cached length; its key and value are appended to the cache
+ * (KV-cached generation, Sec. V-A workload).
+ *   hidden_in / hidden_out  device, [batch, hidden]; may alias.
+ * Asynchronous on the stage's stream.
+ * Errors: HYP_ESTATE (no prefill yet), HYP_ECAPACITY (some request already holds
+ * max_seq tokens; nothing is changed), HYP_EINVAL, HYP_EDEVICE. */
+HYP_API hyp_status_t stage_decode_step(hyp_stage_t *stage, const void *hidden_in, void *hidden_out);
+
+/* Copy the cached keys (post-RoPE) and values of one request and one block of
+ * the stage (layer in [0, l_end - l_start)) to k_out / v_out, device,
+ * [context_len, n_kv_heads*head_dim] row-major in the stage dtype.  This is what
+ * a request needs to move to another node of the same tier.  Asynchronous.
+ * Errors: HYP_EINVAL, HYP_ESTATE (no such request). */
+HYP_API hyp_status_t stage_export_kv(hyp_stage_t *stage, int32_t layer, int32_t request, void *k_out,
+                             void *v_out);
+
+/* Tokens cached for `request` (host value, counts enqueued steps). */
+HYP_API hyp_status_t stage_context_len(const hyp_stage_t *stage, int32_t request, int32_t *len_out);
+
+/* Release host state.  The workspace returns to the caller, who must first
+ * synchronise the stream.  stage_destroy(NULL) is HYP_EINVAL; destroying the
+ * same pointer twice is undefined, like free(). */
+HYP_API hyp_status_t stage_destroy(hyp_stage_t *stage);
+
+/* Message of the last failing call on this stage (or, with stage == NULL, of the
+ * last failing stage_create / stage_workspace_bytes on this thread).  Owned by
+ * the library, valid until the next call; never NULL. */
+HYP_API const char *stage_last_error(const hyp_stage_t *stage);
+
+/* 1 if the MFMA kernels run for this stage, 0 if the shape-generic kernels do
+ * (fp32 stages, head_dim != 128, widths that are not multiples of 256, or
+ * HYP_FLAG_PLAIN_KERNELS). */
+HYP_API int32_t stage_uses_mfma(const hyp_stage_t *stage);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYP_STAGE_H */

@@ -1,0 +1,12 @@
+"""MI355X-native forward pass of one pipeline stage of decoder blocks.
+
+The work is done by the HIP library `libhyp_stage.so` (C ABI in
+include/hyp_stage.h); this package only marshals arguments.  Importing the
+package does not load the library; the first call does, and fails loudly if it
+has not been built (python -m paper_2511_14450_amd.build).
+"""
+from .binding import (  # noqa: F401
+    HypError, LayerWeights, Stage, StageConfig, library_path, load_library,
+    stage_context_len, stage_create, stage_decode_step, stage_destroy, stage_export_kv,
+    stage_last_error, stage_prefill, stage_uses_mfma, stage_workspace_bytes,
+)

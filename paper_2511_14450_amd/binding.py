@@ -1,0 +1,227 @@
+"""ctypes binding of include/hyp_stage.h: same names, argument marshalling only.
+
+PyTorch appears here solely as the owner of device memory and streams; every
+step of the stage runs inside the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import pathlib
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_PKG = pathlib.Path(__file__).resolve().parent
+_LIB: Optional[C.CDLL] = None
+
+HYP_OK, HYP_EINVAL, HYP_ESHAPE, HYP_ECAPACITY, HYP_ESTATE, HYP_EDEVICE, HYP_ENOMEM = range(7)
+STATUS_NAMES = ["HYP_OK", "HYP_EINVAL", "HYP_ESHAPE", "HYP_ECAPACITY", "HYP_ESTATE", "HYP_EDEVICE", "HYP_ENOMEM"]
+HYP_F32, HYP_BF16 = 0, 1
+HYP_FLAG_PLAIN_KERNELS = 1
+
+EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_decode_step",
+           "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",
+           "stage_uses_mfma")
+
+
+class HypError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 7 else status}: {message}")
+        self.status = status
+
+
+class StageConfig(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn_dim", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_batch", C.c_int32),
+                ("max_seq", C.c_int32), ("max_prefill_tokens", C.c_int64), ("flags", C.c_uint32),
+                ("reserved", C.c_uint32)]
+
+
+_WEIGHT_FIELDS = ("attn_norm_g", "wq", "wk", "wv", "wo", "ffn_norm_g", "w_gate", "w_up", "w_down")
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
+
+
+def library_path() -> pathlib.Path:
+    return _PKG / "libhyp_stage.so"
+
+
+def load_library() -> C.CDLL:
+    """Load libhyp_stage.so; raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not path.exists():
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2511_14450_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(str(path))
+    lib.stage_workspace_bytes.restype = C.c_size_t
+    lib.stage_workspace_bytes.argtypes = [C.POINTER(StageConfig), C.c_int32, C.c_int32]
+    lib.stage_create.restype = C.c_int
+    lib.stage_create.argtypes = [C.POINTER(StageConfig), C.c_int32, C.c_int32, C.POINTER(LayerWeights),
+                                 C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.stage_prefill.restype = C.c_int
+    lib.stage_prefill.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
+    lib.stage_decode_step.restype = C.c_int
+    lib.stage_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.stage_export_kv.restype = C.c_int
+    lib.stage_export_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.stage_context_len.restype = C.c_int
+    lib.stage_context_len.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    lib.stage_destroy.restype = C.c_int
+    lib.stage_destroy.argtypes = [C.c_void_p]
+    lib.stage_last_error.restype = C.c_char_p
+    lib.stage_last_error.argtypes = [C.c_void_p]
+    lib.stage_uses_mfma.restype = C.c_int32
+    lib.stage_uses_mfma.argtypes = [C.c_void_p]
+    _LIB = lib
+    return lib
+
+
+def _torch_dtype(dtype: int):
+    return torch.bfloat16 if dtype == HYP_BF16 else torch.float32
+
+
+def _check(status: int, handle) -> None:
+    if status != HYP_OK:
+        raise HypError(status, stage_last_error(handle))
+
+
+def stage_last_error(handle) -> str:
+    return load_library().stage_last_error(handle).decode()
+
+
+def stage_workspace_bytes(cfg: StageConfig, l_start: int, l_end: int) -> int:
+    return int(load_library().stage_workspace_bytes(C.byref(cfg), l_start, l_end))
+
+
+class Stage:
+    """Handle plus the tensors that must outlive it (workspace, stream)."""
+
+    def __init__(self, handle, cfg: StageConfig, workspace: torch.Tensor, stream, l_start: int, l_end: int):
+        self.handle, self.cfg, self.workspace, self.stream = handle, cfg, workspace, stream
+        self.l_start, self.l_end = l_start, l_end
+
+    # method spellings of the module-level calls
+    def prefill(self, hidden_in, seq_lens, hidden_out=None):
+        return stage_prefill(self, hidden_in, seq_lens, hidden_out)
+
+    def decode_step(self, hidden_in, hidden_out=None):
+        return stage_decode_step(self, hidden_in, hidden_out)
+
+    def export_kv(self, layer, request):
+        return stage_export_kv(self, layer, request)
+
+    def context_len(self, request):
+        return stage_context_len(self, request)
+
+    def uses_mfma(self):
+        return stage_uses_mfma(self)
+
+    def destroy(self):
+        stage_destroy(self)
+
+    def __del__(self):
+        try:
+            if self.handle:
+                stage_destroy(self)
+        except Exception:
+            pass
+
+
+def stage_create(cfg: StageConfig, l_start: int, l_end: int, layers: Sequence[Dict[str, torch.Tensor]],
+                 stream: Optional[torch.cuda.Stream] = None, workspace: Optional[torch.Tensor] = None) -> Stage:
+    """layers[i][name] are device tensors of the config dtype, shapes as in hyp_layer_weights_t."""
+    lib = load_library()
+    need = stage_workspace_bytes(cfg, l_start, l_end)
+    if need == 0:
+        # let stage_create produce the precise status
+        need = 256
+    dt = _torch_dtype(cfg.dtype)
+    n = len(layers)
+    arr = (LayerWeights * max(n, 1))()
+    keep = []
+    for i, w in enumerate(layers):
+        for name in _WEIGHT_FIELDS:
+            t = w[name]
+            if t is None:
+                setattr(arr[i], name, None)
+                continue
+            if not t.is_cuda or t.dtype != dt or not t.is_contiguous():
+                raise ValueError(f"layer {i} {name}: need a contiguous {dt} device tensor")
+            keep.append(t)
+            setattr(arr[i], name, t.data_ptr())
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
+    stream = stream if stream is not None else torch.cuda.current_stream()
+    handle = C.c_void_p()
+    status = lib.stage_create(C.byref(cfg), l_start, l_end, arr, workspace.data_ptr(), workspace.numel(),
+                              C.c_void_p(stream.cuda_stream), C.byref(handle))
+    _check(status, None)
+    del keep  # stage_create returns after the weights were copied
+    return Stage(handle, cfg, workspace, stream, l_start, l_end)
+
+
+def stage_prefill(stage: Stage, hidden_in: torch.Tensor, seq_lens: Sequence[int],
+                  hidden_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    lens = (C.c_int32 * len(seq_lens))(*[int(v) for v in seq_lens])
+    if hidden_out is None:
+        hidden_out = torch.empty_like(hidden_in)
+    _validate_io(stage, hidden_in, hidden_out, sum(int(v) for v in seq_lens))
+    status = load_library().stage_prefill(stage.handle, hidden_in.data_ptr(), lens, len(seq_lens),
+                                          hidden_out.data_ptr())
+    _check(status, stage.handle)
+    return hidden_out
+
+
+def stage_decode_step(stage: Stage, hidden_in: torch.Tensor, hidden_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if hidden_out is None:
+        hidden_out = torch.empty_like(hidden_in)
+    _validate_io(stage, hidden_in, hidden_out, None)
+    status = load_library().stage_decode_step(stage.handle, hidden_in.data_ptr(), hidden_out.data_ptr())
+    _check(status, stage.handle)
+    return hidden_out
+
+
+def _validate_io(stage: Stage, a: torch.Tensor, b: torch.Tensor, rows: Optional[int]) -> None:
+    dt = _torch_dtype(stage.cfg.dtype)
+    for t in (a, b):
+        if not t.is_cuda or t.dtype != dt or not t.is_contiguous() or t.dim() != 2 or t.shape[1] != stage.cfg.hidden:
+            raise ValueError(f"hidden states must be contiguous {dt} device tensors [rows, {stage.cfg.hidden}]")
+    if a.shape != b.shape or (rows is not None and a.shape[0] != rows):
+        raise ValueError("hidden_in / hidden_out row count does not match the request lengths")
+
+
+def stage_context_len(stage: Stage, request: int) -> int:
+    out = C.c_int32()
+    status = load_library().stage_context_len(stage.handle, request, C.byref(out))
+    if status != HYP_OK:
+        raise HypError(status, "no such request")
+    return out.value
+
+
+def stage_export_kv(stage: Stage, layer: int, request: int):
+    n = stage_context_len(stage, request)
+    kvd = stage.cfg.n_kv_heads * stage.cfg.head_dim
+    k = torch.empty((n, kvd), dtype=_torch_dtype(stage.cfg.dtype), device="cuda")
+    v = torch.empty_like(k)
+    status = load_library().stage_export_kv(stage.handle, layer, request, k.data_ptr(), v.data_ptr())
+    _check(status, stage.handle)
+    return k, v
+
+
+def stage_uses_mfma(stage: Stage) -> bool:
+    return bool(load_library().stage_uses_mfma(stage.handle))
+
+
+def stage_destroy(stage: Stage) -> None:
+    if stage.handle:
+        stage.stream.synchronize()
+        status = load_library().stage_destroy(stage.handle)
+        stage.handle = None
+        if status != HYP_OK:
+            raise HypError(status, "stage_destroy failed")

@@ -1,0 +1,385 @@
+// Host runtime behind the C ABI of hyp_stage.h: argument checking, workspace
+// carving, weight repacking, the block loop (Eq. 1) over the stage's range
+// (Eq. 6) for prefill and for KV-cached decode steps.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace hyp;
+
+namespace {
+
+thread_local std::string g_create_error = "";
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct LayerPtrs {
+  size_t g1, wqkv, wo, g2, wgu, wd;  // offsets into the workspace
+};
+
+// Where everything lives inside the caller's workspace.
+struct Layout {
+  std::vector<LayerPtrs> layers;
+  size_t Kc, Vc, kv_layer_stride;  // per-layer stride in bytes
+  size_t cos_tab, sin_tab;
+  size_t xres, y, qkv, attn, gu, m;
+  size_t tok_req, tok_pos, lens, iota;
+  size_t total;
+};
+
+size_t elem_size(const hyp_stage_config_t &c) { return c.dtype == HYP_BF16 ? 2 : 4; }
+
+int64_t max_rows(const hyp_stage_config_t &c) {
+  return c.max_prefill_tokens > c.max_batch ? c.max_prefill_tokens : (int64_t)c.max_batch;
+}
+
+hyp_status_t check_config(const hyp_stage_config_t *c, int32_t l_start, int32_t l_end,
+                          std::string &err) {
+  if (!c) { err = "config is NULL"; return HYP_EINVAL; }
+  if (l_start < 0 || l_start >= l_end) { err = "need 0 <= l_start < l_end"; return HYP_EINVAL; }
+  if (c->dtype != HYP_F32 && c->dtype != HYP_BF16) { err = "dtype must be HYP_F32 or HYP_BF16"; return HYP_EINVAL; }
+  if (c->reserved != 0) { err = "reserved must be 0"; return HYP_EINVAL; }
+  if (c->hidden < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 2 || c->ffn_dim < 1 ||
+      c->max_batch < 1 || c->max_seq < 1 || c->max_prefill_tokens < 1) {
+    err = "sizes must be positive"; return HYP_ESHAPE;
+  }
+  if (c->n_q_heads % c->n_kv_heads != 0) { err = "n_kv_heads must divide n_q_heads"; return HYP_ESHAPE; }
+  if (c->head_dim % 2 != 0) { err = "head_dim must be even (RoPE pairs)"; return HYP_ESHAPE; }
+  if (c->head_dim > 256) { err = "head_dim above 256 is not supported"; return HYP_ESHAPE; }
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) { err = "rms_eps must be >= 0 and rope_base > 0"; return HYP_ESHAPE; }
+  if (c->max_prefill_tokens > (int64_t)c->max_batch * c->max_seq) {
+    err = "max_prefill_tokens exceeds max_batch * max_seq"; return HYP_ESHAPE;
+  }
+  if (c->max_prefill_tokens > (int64_t)1 << 30) { err = "max_prefill_tokens too large"; return HYP_ESHAPE; }
+  return HYP_OK;
+}
+
+void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
+  size_t es = elem_size(c);
+  size_t H = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim;
+  size_t I = c.ffn_dim, R = (size_t)max_rows(c);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  L.layers.resize(n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    LayerPtrs &p = L.layers[l];
+    p.g1 = take(es * H);
+    p.wqkv = take(es * (qd + 2 * kvd) * H);
+    p.wo = take(es * H * qd);
+    p.g2 = take(es * H);
+    p.wgu = take(es * 2 * I * H);
+    p.wd = take(es * H * I);
+  }
+  L.kv_layer_stride = align_up(es * (size_t)c.max_batch * kvd * c.max_seq);
+  L.Kc = take(L.kv_layer_stride * n_layers);
+  L.Vc = take(L.kv_layer_stride * n_layers);
+  size_t tab = sizeof(float) * (size_t)c.max_seq * (c.head_dim / 2);
+  L.cos_tab = take(tab);
+  L.sin_tab = take(tab);
+  L.xres = take(sizeof(float) * R * H);
+  L.y = take(es * R * H);
+  L.qkv = take(es * R * (qd + 2 * kvd));
+  L.attn = take(es * R * qd);
+  L.gu = take(es * R * 2 * I);
+  L.m = take(es * R * I);
+  L.tok_req = take(sizeof(int) * R);
+  L.tok_pos = take(sizeof(int) * R);
+  L.lens = take(sizeof(int) * c.max_batch);
+  L.iota = take(sizeof(int) * c.max_batch);
+  L.total = off;
+}
+
+}  // namespace
+
+struct hyp_stage {
+  hyp_stage_config_t cfg;
+  int l_start, l_end, n_layers;
+  Dims dm;
+  hipStream_t stream;
+  bool bf16, mfma;
+  char *ws;
+  Layout L;
+  // pinned host staging for the per-call index arrays, and the event that says
+  // the previous upload has been consumed
+  int *h_stage;
+  size_t h_stage_ints;
+  hipEvent_t upload_done;
+  bool upload_pending;
+  std::vector<int> lens;  // host mirror of the cached lengths
+  int batch;
+  bool prefilled;
+  std::string err;
+};
+
+namespace {
+
+hyp_status_t fail(hyp_stage *st, hyp_status_t code, const std::string &msg) {
+  if (st) st->err = msg; else g_create_error = msg;
+  return code;
+}
+
+#define HIP_TRY(st, expr)                                                                        \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess)                                                                        \
+      return fail(st, HYP_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_));           \
+  } while (0)
+
+template <typename T> T *at(hyp_stage *st, size_t off) { return reinterpret_cast<T *>(st->ws + off); }
+
+// Copy the caller's matrices into the workspace: wq|wk|wv stacked into one
+// [qd+2kvd, H] matrix and gate|up into one [2I, H] matrix.
+hyp_status_t copy_weights(hyp_stage *st, const hyp_layer_weights_t *layers) {
+  size_t es = st->bf16 ? 2 : 4;
+  const Dims &d = st->dm;
+  for (int l = 0; l < st->n_layers; ++l) {
+    const hyp_layer_weights_t &w = layers[l];
+    const void *ptrs[] = {w.attn_norm_g, w.wq, w.wk, w.wv, w.wo, w.ffn_norm_g, w.w_gate, w.w_up, w.w_down};
+    for (const void *p : ptrs)
+      if (!p) return fail(st, HYP_EINVAL, "a weight pointer of layer " + std::to_string(l) + " is NULL");
+    const LayerPtrs &p = st->L.layers[l];
+    auto cp = [&](size_t dst, const void *src, size_t bytes) {
+      return hipMemcpyAsync(st->ws + dst, src, bytes, hipMemcpyDeviceToDevice, st->stream);
+    };
+    size_t H = d.H;
+    HIP_TRY(st, cp(p.g1, w.attn_norm_g, es * H));
+    HIP_TRY(st, cp(p.wqkv, w.wq, es * d.qd * H));
+    HIP_TRY(st, cp(p.wqkv + es * d.qd * H, w.wk, es * d.kvd * H));
+    HIP_TRY(st, cp(p.wqkv + es * (d.qd + d.kvd) * H, w.wv, es * d.kvd * H));
+    HIP_TRY(st, cp(p.wo, w.wo, es * H * d.qd));
+    HIP_TRY(st, cp(p.g2, w.ffn_norm_g, es * H));
+    HIP_TRY(st, cp(p.wgu, w.w_gate, es * (size_t)d.I * H));
+    HIP_TRY(st, cp(p.wgu + es * (size_t)d.I * H, w.w_up, es * (size_t)d.I * H));
+    HIP_TRY(st, cp(p.wd, w.w_down, es * H * (size_t)d.I));
+  }
+  return HYP_OK;
+}
+
+// rows tokens through every block with the shape-generic kernels
+template <typename T>
+hyp_status_t run_plain(hyp_stage *st, const void *hidden_in, void *hidden_out, int rows,
+                       const int *tok_req, const int *tok_pos) {
+  const Dims &d = st->dm;
+  hipStream_t s = st->stream;
+  float *xres = at<float>(st, st->L.xres);
+  T *y = at<T>(st, st->L.y), *qkv = at<T>(st, st->L.qkv), *attn = at<T>(st, st->L.attn);
+  T *gu = at<T>(st, st->L.gu), *m = at<T>(st, st->L.m);
+  const float *ct = at<float>(st, st->L.cos_tab), *sn = at<float>(st, st->L.sin_tab);
+  HIP_TRY(st, plain_load_hidden<T>((const T *)hidden_in, xres, (size_t)rows * d.H, s));
+  for (int l = 0; l < st->n_layers; ++l) {
+    const LayerPtrs &p = st->L.layers[l];
+    T *Kc = at<T>(st, st->L.Kc + st->L.kv_layer_stride * l);
+    T *Vc = at<T>(st, st->L.Vc + st->L.kv_layer_stride * l);
+    HIP_TRY(st, plain_rmsnorm<T>(xres, at<T>(st, p.g1), y, rows, d.H, d.eps, s));
+    HIP_TRY(st, (plain_gemm_nt<T, T>(y, at<T>(st, p.wqkv), qkv, rows, d.qd + 2 * d.kvd, d.H, false, s)));
+    HIP_TRY(st, plain_rope_cache<T>(qkv, tok_req, tok_pos, ct, sn, Kc, Vc, rows, d, s));
+    HIP_TRY(st, plain_attention<T>(qkv, tok_req, tok_pos, Kc, Vc, attn, rows, d, s));
+    HIP_TRY(st, (plain_gemm_nt<T, float>(attn, at<T>(st, p.wo), xres, rows, d.H, d.qd, true, s)));
+    HIP_TRY(st, plain_rmsnorm<T>(xres, at<T>(st, p.g2), y, rows, d.H, d.eps, s));
+    HIP_TRY(st, (plain_gemm_nt<T, T>(y, at<T>(st, p.wgu), gu, rows, 2 * d.I, d.H, false, s)));
+    HIP_TRY(st, plain_swiglu<T>(gu, m, rows, d.I, s));
+    HIP_TRY(st, (plain_gemm_nt<T, float>(m, at<T>(st, p.wd), xres, rows, d.H, d.I, true, s)));
+  }
+  HIP_TRY(st, plain_store_hidden<T>(xres, (T *)hidden_out, (size_t)rows * d.H, s));
+  return HYP_OK;
+}
+
+hyp_status_t wait_upload(hyp_stage *st) {
+  if (st->upload_pending) {
+    HIP_TRY(st, hipEventSynchronize(st->upload_done));
+    st->upload_pending = false;
+  }
+  return HYP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t stage_workspace_bytes(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end) {
+  std::string err;
+  if (check_config(cfg, l_start, l_end, err) != HYP_OK) { g_create_error = err; return 0; }
+  Layout L;
+  make_layout(*cfg, l_end - l_start, L);
+  return L.total;
+}
+
+hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end,
+                          const hyp_layer_weights_t *layers, void *workspace, size_t workspace_bytes,
+                          void *hip_stream, hyp_stage_t **out) {
+  if (out) *out = nullptr;
+  std::string err;
+  hyp_status_t rc = check_config(cfg, l_start, l_end, err);
+  if (rc != HYP_OK) return fail(nullptr, rc, err);
+  if (!layers || !workspace || !out) return fail(nullptr, HYP_EINVAL, "layers, workspace and out must not be NULL");
+  if ((uintptr_t)workspace % kAlign != 0) return fail(nullptr, HYP_ENOMEM, "workspace must be 256-byte aligned");
+
+  hyp_stage *st = new (std::nothrow) hyp_stage();
+  if (!st) return fail(nullptr, HYP_ENOMEM, "host allocation failed");
+  st->cfg = *cfg;
+  st->l_start = l_start; st->l_end = l_end; st->n_layers = l_end - l_start;
+  st->stream = (hipStream_t)hip_stream;
+  st->bf16 = cfg->dtype == HYP_BF16;
+  st->mfma = false;
+  st->ws = (char *)workspace;
+  st->h_stage = nullptr; st->upload_done = nullptr; st->upload_pending = false;
+  st->batch = 0; st->prefilled = false;
+  Dims &d = st->dm;
+  d.H = cfg->hidden; d.nq = cfg->n_q_heads; d.nkv = cfg->n_kv_heads; d.d = cfg->head_dim;
+  d.I = cfg->ffn_dim; d.qd = d.nq * d.d; d.kvd = d.nkv * d.d;
+  d.max_batch = cfg->max_batch; d.max_seq = cfg->max_seq; d.eps = cfg->rms_eps;
+  make_layout(*cfg, st->n_layers, st->L);
+  if (workspace_bytes < st->L.total) {
+    std::string m = "workspace too small: need " + std::to_string(st->L.total) + " bytes";
+    delete st;
+    return fail(nullptr, HYP_ENOMEM, m);
+  }
+
+  auto bail = [&](hyp_status_t code) {
+    g_create_error = st->err;
+    if (st->upload_done) (void)hipEventDestroy(st->upload_done);
+    if (st->h_stage) (void)hipHostFree(st->h_stage);
+    delete st;
+    return code;
+  };
+
+  st->h_stage_ints = 2 * (size_t)max_rows(*cfg) + 2 * (size_t)cfg->max_batch;
+  if (hipHostMalloc((void **)&st->h_stage, sizeof(int) * st->h_stage_ints, hipHostMallocDefault) != hipSuccess) {
+    st->h_stage = nullptr; st->err = "hipHostMalloc failed";
+    return bail(HYP_ENOMEM);
+  }
+  if (hipEventCreateWithFlags(&st->upload_done, hipEventDisableTiming) != hipSuccess) {
+    st->upload_done = nullptr; st->err = "hipEventCreate failed";
+    return bail(HYP_EDEVICE);
+  }
+
+  rc = copy_weights(st, layers);
+  if (rc != HYP_OK) return bail(rc);
+
+  // RoPE tables: angle = pos * base^(-2i/d), formed in double on the host
+  {
+    int half = d.d / 2;
+    std::vector<float> ct((size_t)d.max_seq * half), sn((size_t)d.max_seq * half);
+    for (int i = 0; i < half; ++i) {
+      double theta = pow((double)cfg->rope_base, -2.0 * (double)i / (double)d.d);
+      for (int p = 0; p < d.max_seq; ++p) {
+        double a = (double)p * theta;
+        ct[(size_t)p * half + i] = (float)cos(a);
+        sn[(size_t)p * half + i] = (float)sin(a);
+      }
+    }
+    hipError_t e = hipMemcpyAsync(st->ws + st->L.cos_tab, ct.data(), sizeof(float) * ct.size(), hipMemcpyHostToDevice, st->stream);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(st->ws + st->L.sin_tab, sn.data(), sizeof(float) * sn.size(), hipMemcpyHostToDevice, st->stream);
+    std::vector<int> iota(cfg->max_batch);
+    for (int i = 0; i < cfg->max_batch; ++i) iota[i] = i;
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(st->ws + st->L.iota, iota.data(), sizeof(int) * iota.size(), hipMemcpyHostToDevice, st->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(st->stream);  // host vectors die here
+    if (e != hipSuccess) { st->err = std::string("table upload: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
+  }
+  *out = st;
+  return HYP_OK;
+}
+
+hyp_status_t stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t *seq_lens,
+                           int32_t batch, void *hidden_out) {
+  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+  if (!hidden_in || !seq_lens || !hidden_out) return fail(st, HYP_EINVAL, "NULL argument");
+  if (batch < 1 || batch > st->cfg.max_batch) return fail(st, HYP_ECAPACITY, "batch outside 1..max_batch");
+  int64_t total = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (seq_lens[b] < 1 || seq_lens[b] > st->cfg.max_seq)
+      return fail(st, HYP_ECAPACITY, "seq_lens[" + std::to_string(b) + "] outside 1..max_seq");
+    total += seq_lens[b];
+  }
+  if (total > st->cfg.max_prefill_tokens) return fail(st, HYP_ECAPACITY, "sum(seq_lens) exceeds max_prefill_tokens");
+  int rows = (int)total;
+
+  hyp_status_t rc = wait_upload(st);
+  if (rc != HYP_OK) return rc;
+  int *h_req = st->h_stage, *h_pos = st->h_stage + rows, *h_len = st->h_stage + 2 * (size_t)rows;
+  {
+    int t = 0;
+    for (int b = 0; b < batch; ++b)
+      for (int p = 0; p < seq_lens[b]; ++p, ++t) { h_req[t] = b; h_pos[t] = p; }
+    for (int b = 0; b < batch; ++b) h_len[b] = seq_lens[b];
+  }
+  hipStream_t s = st->stream;
+  HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.tok_req, h_req, sizeof(int) * rows, hipMemcpyHostToDevice, s));
+  HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.tok_pos, h_pos, sizeof(int) * rows, hipMemcpyHostToDevice, s));
+  HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.lens, h_len, sizeof(int) * batch, hipMemcpyHostToDevice, s));
+  HIP_TRY(st, hipEventRecord(st->upload_done, s));
+  st->upload_pending = true;
+
+  const int *tok_req = at<int>(st, st->L.tok_req), *tok_pos = at<int>(st, st->L.tok_pos);
+  rc = st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, rows, tok_req, tok_pos)
+                : run_plain<float>(st, hidden_in, hidden_out, rows, tok_req, tok_pos);
+  if (rc != HYP_OK) return rc;
+  st->lens.assign(seq_lens, seq_lens + batch);
+  st->batch = batch;
+  st->prefilled = true;
+  return HYP_OK;
+}
+
+hyp_status_t stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
+  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+  if (!hidden_in || !hidden_out) return fail(st, HYP_EINVAL, "NULL argument");
+  if (!st->prefilled) return fail(st, HYP_ESTATE, "stage_decode_step before stage_prefill");
+  for (int b = 0; b < st->batch; ++b)
+    if (st->lens[b] >= st->cfg.max_seq)
+      return fail(st, HYP_ECAPACITY, "request " + std::to_string(b) + " already holds max_seq tokens");
+  const int *iota = at<int>(st, st->L.iota), *lens = at<int>(st, st->L.lens);
+  hyp_status_t rc = st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, st->batch, iota, lens)
+                             : run_plain<float>(st, hidden_in, hidden_out, st->batch, iota, lens);
+  if (rc != HYP_OK) return rc;
+  HIP_TRY(st, advance_lens(at<int>(st, st->L.lens), st->batch, st->stream));
+  for (int b = 0; b < st->batch; ++b) st->lens[b] += 1;
+  return HYP_OK;
+}
+
+hyp_status_t stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {
+  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+  if (!k_out || !v_out) return fail(st, HYP_EINVAL, "NULL argument");
+  if (layer < 0 || layer >= st->n_layers) return fail(st, HYP_EINVAL, "layer outside the stage");
+  if (!st->prefilled || request < 0 || request >= st->batch) return fail(st, HYP_ESTATE, "no such request");
+  size_t off = st->L.kv_layer_stride * layer;
+  int len = st->lens[request];
+  if (st->bf16)
+    HIP_TRY(st, plain_export_kv<bf16_t>(at<bf16_t>(st, st->L.Kc + off), at<bf16_t>(st, st->L.Vc + off),
+                                        (bf16_t *)k_out, (bf16_t *)v_out, request, len, st->dm, st->stream));
+  else
+    HIP_TRY(st, plain_export_kv<float>(at<float>(st, st->L.Kc + off), at<float>(st, st->L.Vc + off),
+                                       (float *)k_out, (float *)v_out, request, len, st->dm, st->stream));
+  return HYP_OK;
+}
+
+hyp_status_t stage_context_len(const hyp_stage_t *st, int32_t request, int32_t *len_out) {
+  if (!st || !len_out) return HYP_EINVAL;
+  if (!st->prefilled || request < 0 || request >= st->batch) return HYP_ESTATE;
+  *len_out = st->lens[request];
+  return HYP_OK;
+}
+
+hyp_status_t stage_destroy(hyp_stage_t *st) {
+  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+  if (st->upload_done) (void)hipEventDestroy(st->upload_done);
+  if (st->h_stage) (void)hipHostFree(st->h_stage);
+  delete st;
+  return HYP_OK;
+}
+
+const char *stage_last_error(const hyp_stage_t *st) {
+  return st ? st->err.c_str() : g_create_error.c_str();
+}
+
+int32_t stage_uses_mfma(const hyp_stage_t *st) { return st && st->mfma ? 1 : 0; }
+
+}  // extern "C"

@@ -1,0 +1,307 @@
+// Attention kernels of the MFMA path: causal grouped-query attention over the
+// prompt (flash-style: the score matrix is never written), and split-KV
+// attention of one new token per request against the cache (bandwidth-bound).
+// Both follow the GQA-with-RoPE sub-layer of Sec. III-A; RoPE was already
+// applied to q and to the cached keys by the QKV epilogue.
+#include "mfma_common.h"
+#include "mfma_kernels.h"
+
+namespace hyp {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ float xhalf_max(float v) { return fmaxf(v, __shfl_xor(v, 32, 64)); }
+__device__ __forceinline__ float xhalf_sum(float v) { return v + __shfl_xor(v, 32, 64); }
+
+__device__ __forceinline__ bf16x8_t probs_operand(const float *p /*16*/, int m) {
+  // MFMA step m of the P V product contracts keys 16m + 8(e/4) + 4hh + e%4: registers 8m .. 8m+7
+  bf16x8_t r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (__bf16)p[8 * m + e];
+  return r;
+}
+
+// ----------------------------------------------------------------------------
+// Prefill.  One workgroup = one KV head x one tile of 64 query rows; its G waves
+// are the G query heads that share the KV head, so each 32-key block of K and V
+// (16 KiB, already in fragment order) is fetched once into LDS by direct loads
+// and read by all G waves.  Per wave: S^T = K Q^T (keys on the MFMA M axis, so a
+// lane owns one query column and the softmax reductions stay inside a lane plus
+// one cross-half exchange), online softmax in fp32, O^T += V^T P^T.
+// ----------------------------------------------------------------------------
+constexpr int kKvBlockBytes = 16384;  // 8 K tiles + 8 V tiles
+
+__global__ void __launch_bounds__(256) k_attn_prefill(const bf16_t *__restrict__ q,
+                                                      const bf16_t *__restrict__ Kc,
+                                                      const bf16_t *__restrict__ Vc, CacheGeom geom,
+                                                      bf16_t *__restrict__ out,
+                                                      const PrefillTile *__restrict__ tiles,
+                                                      const int *__restrict__ req_len, int nq, int G) {
+  __shared__ __attribute__((aligned(1024))) char lds[2 * kKvBlockBytes];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hh = lane >> 5, tl = lane & 31;
+  const PrefillTile tile = tiles[blockIdx.x];
+  const int kvh = blockIdx.y;
+  const int head = kvh * G + wave;
+  const int qd = nq * 128;
+  const int len = req_len[tile.req];
+  const int n_kb = min(tile.qblk0 + 2, (len + 31) >> 5);
+  const int rb0 = tile.row0 >> 5;
+  const float c = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
+
+  // query fragments of this head: B operand, 2 query blocks x 8 k-tiles
+  bf16x8_t qf[2][8];
+#pragma unroll
+  for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+      qf[tq][dt] = *(const bf16x8_t *)(q + ((size_t)(rb0 + tq) * (qd >> 4) + head * 8 + dt) * kTileElems + lane * 8);
+
+  f32x16_t o[4][2];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[db][tq][r] = 0.f;
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+
+  const int nw = blockDim.x >> 6;
+  auto issue = [&](int kb, int buf) {
+    // 16 tiles of 1 KiB, spread over the waves
+    for (int t = wave; t < 16; t += nw) {
+      const bf16_t *src = (t < 8 ? Kc : Vc) + geom.off(tile.req, kvh, kb) + (size_t)(t & 7) * kTileElems + lane * 8;
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvBlockBytes + t * 1024), 16, 0, 0);
+    }
+  };
+  issue(0, 0);
+  for (int kb = 0; kb < n_kb; ++kb) {
+    const int buf = kb & 1;
+    __builtin_amdgcn_s_waitcnt(0x0070);  // my loads landed, my LDS reads of the previous block done
+    __syncthreads();
+    if (kb + 1 < n_kb) issue(kb + 1, buf ^ 1);
+    const char *base = lds + buf * kKvBlockBytes + lane * 16;
+
+    // scores S^T[key, query]
+    f32x16_t s[2];
+#pragma unroll
+    for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[tq][r] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      bf16x8_t kf = *(const bf16x8_t *)(base + dt * 1024);
+#pragma unroll
+      for (int tq = 0; tq < 2; ++tq) s[tq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[tq][dt], s[tq], 0, 0, 0);
+    }
+
+    bf16x8_t pf[2][2];
+#pragma unroll
+    for (int tq = 0; tq < 2; ++tq) {
+      float p[16];
+      const int qpos = (tile.qblk0 + tq) * 32 + tl;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = s[tq][r];
+        if (kb >= tile.qblk0) {  // only the last two key blocks touch the diagonal
+          int kpos = kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+          if (kpos > qpos) v = -INFINITY;
+        }
+        p[r] = v;
+        mx = fmaxf(mx, v);
+      }
+      mx = xhalf_max(mx);
+      float m_new = fmaxf(m_run[tq], mx);  // finite from the first block on: key 0 is visible to every row
+      float rowsum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        p[r] = exp2f((p[r] - m_new) * c);
+        rowsum += p[r];
+      }
+      if (__any(m_new > m_run[tq])) {
+        float alpha = exp2f((m_run[tq] - m_new) * c);  // 0 on the first block
+        l_run[tq] *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][tq][r] *= alpha;
+        m_run[tq] = m_new;
+      }
+      l_run[tq] += rowsum;
+      pf[tq][0] = probs_operand(p, 0);
+      pf[tq][1] = probs_operand(p, 1);
+    }
+
+    // O^T[d, query] += V^T P^T
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        bf16x8_t vf = *(const bf16x8_t *)(base + (8 + m * 4 + db) * 1024);
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq) o[db][tq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tq][m], o[db][tq], 0, 0, 0);
+      }
+  }
+
+  // normalise and store into P(rows, qd): lane owns query tl, features 8g + 4hh + e of each d block
+#pragma unroll
+  for (int tq = 0; tq < 2; ++tq) {
+    float inv = 1.0f / xhalf_sum(l_run[tq]);
+    int tb = rb0 + tq;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int f0 = head * 128 + db * 32;
+        size_t off = ((size_t)tb * (qd >> 4) + ((f0 + 8 * g) >> 4)) * kTileElems + (((g & 1) << 5) + tl) * 8 + hh * 4;
+        *(bf16x4_t *)(out + off) = pack4(o[db][tq][4 * g] * inv, o[db][tq][4 * g + 1] * inv,
+                                         o[db][tq][4 * g + 2] * inv, o[db][tq][4 * g + 3] * inv);
+      }
+  }
+}
+
+// ----------------------------------------------------------------------------
+// Decode.  The query buffer holds, per (request, KV head), the G query heads as
+// rows 0..G-1 of a P(32, 128) block (other rows zero), so the same MFMA shape
+// serves: S^T[key, head] = K q^T.  K and V fragments go straight from HBM into
+// registers (fragment order = operand order), 16 wave loads of 1 KiB per 32-key
+// block, no LDS.  One wave owns a chunk of kDecodeChunkKeys keys of one
+// (request, KV head); chunks balance ragged contexts by tokens.  Every chunk
+// writes (max, sum, unnormalised output) and a second kernel merges the chunks
+// of a head in index order, so the result does not depend on scheduling.
+// part layout: [request][head][chunk][130] = {m, l, o[128]}
+// ----------------------------------------------------------------------------
+constexpr int kPartStride = 130;
+
+__global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ qdec,
+                                                    const bf16_t *__restrict__ Kc,
+                                                    const bf16_t *__restrict__ Vc, CacheGeom geom,
+                                                    const int *__restrict__ lens, float *__restrict__ part,
+                                                    int nq, int G, int max_chunks) {
+  const int lane = threadIdx.x, hh = lane >> 5, tl = lane & 31;
+  const int chunk = blockIdx.x, kvh = blockIdx.y, req = blockIdx.z;
+  const int nkeys = lens[req] + 1;  // the new token's key is already in the cache
+  const int k0 = chunk * kDecodeChunkKeys;
+  if (k0 >= nkeys) return;
+  const int kb_begin = k0 >> 5;
+  const int kb_end = min((k0 + kDecodeChunkKeys) >> 5, (nkeys + 31) >> 5);
+  const float c = kLog2e * 0.08838834764831845f;
+
+  bf16x8_t qf[8];
+  const bf16_t *qb = qdec + ((size_t)req * geom.nkv + kvh) * (32 * 128);
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) qf[dt] = *(const bf16x8_t *)(qb + dt * kTileElems + lane * 8);
+
+  f32x16_t o[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  for (int kb = kb_begin; kb < kb_end; ++kb) {
+    const bf16_t *kblk = Kc + geom.off(req, kvh, kb) + lane * 8;
+    const bf16_t *vblk = Vc + geom.off(req, kvh, kb) + lane * 8;
+    bf16x8_t kf[8], vf[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) kf[t] = *(const bf16x8_t *)(kblk + t * kTileElems);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) vf[t] = *(const bf16x8_t *)(vblk + t * kTileElems);
+    f32x16_t s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[dt], qf[dt], s, 0, 0, 0);
+    float p[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      int kpos = kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+      float v = kpos < nkeys ? s[r] : -INFINITY;
+      p[r] = v;
+      mx = fmaxf(mx, v);
+    }
+    mx = xhalf_max(mx);
+    float m_new = fmaxf(m_run, mx);  // finite: the first key of a chunk is always valid
+    float alpha = exp2f((m_run - m_new) * c);
+    float rowsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      p[r] = exp2f((p[r] - m_new) * c);
+      rowsum += p[r];
+    }
+    l_run = l_run * alpha + rowsum;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    bf16x8_t pf0 = probs_operand(p, 0), pf1 = probs_operand(p, 1);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], pf0, o[db], 0, 0, 0);
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[4 + db], pf1, o[db], 0, 0, 0);
+    }
+  }
+  // lanes tl < G hold real heads
+  float l_tot = xhalf_sum(l_run);
+  if (tl < G) {
+    int head = kvh * G + tl;
+    float *dst = part + (((size_t)req * nq + head) * max_chunks + chunk) * kPartStride;
+    if (hh == 0) { dst[0] = m_run; dst[1] = l_tot; }
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dst[2 + db * 32 + 8 * (r >> 2) + 4 * hh + (r & 3)] = o[db][r];
+  }
+}
+
+// one 128-thread block per (request, head): combine the chunks in order
+__global__ void __launch_bounds__(128) k_attn_decode_merge(const float *__restrict__ part,
+                                                           const int *__restrict__ lens,
+                                                           bf16_t *__restrict__ out, int nq,
+                                                           int max_chunks) {
+  const int head = blockIdx.x, req = blockIdx.y, d = threadIdx.x;
+  const int n_chunks = (lens[req] + 1 + kDecodeChunkKeys - 1) / kDecodeChunkKeys;
+  const float *src = part + ((size_t)req * nq + head) * max_chunks * kPartStride;
+  const float c = kLog2e * 0.08838834764831845f;
+  float m = -INFINITY;
+  for (int i = 0; i < n_chunks; ++i) m = fmaxf(m, src[i * kPartStride]);
+  float l = 0.f, acc = 0.f;
+  for (int i = 0; i < n_chunks; ++i) {
+    float w = exp2f((src[i * kPartStride] - m) * c);
+    l += w * src[i * kPartStride + 1];
+    acc += w * src[i * kPartStride + 2 + d];
+  }
+  out[frag_offset(req, head * 128 + d, nq * 128)] = f2bf_dev(acc / l);
+}
+
+}  // namespace
+
+hipError_t mfma_attn_prefill(const bf16_t *q, const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom,
+                             bf16_t *out, const PrefillTile *tiles, int n_tiles, const int *req_len,
+                             int nq, int nkv, hipStream_t s) {
+  if (n_tiles == 0) return hipSuccess;
+  int G = nq / nkv;
+  k_attn_prefill<<<dim3(n_tiles, nkv), G * 64, 0, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq, G);
+  return hipGetLastError();
+}
+
+size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks) {
+  return (size_t)batch * nq * max_chunks * kPartStride;
+}
+
+hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom,
+                            const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
+                            int max_chunks, hipStream_t s) {
+  int G = nq / nkv;
+  k_attn_decode<<<dim3(max_chunks, nkv, batch), 64, 0, s>>>(qdec, Kc, Vc, geom, lens, part, nq, G, max_chunks);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k_attn_decode_merge<<<dim3(nq, batch), 128, 0, s>>>(part, lens, out, nq, max_chunks);
+  return hipGetLastError();
+}
+
+}  // namespace hyp

@@ -1,0 +1,423 @@
+// MFMA kernels of the prefill path of a bf16 stage: weight repacking, the fused
+// residual-add + RMS Norm, the LDS-staged GEMM with its three epilogues
+// (RoPE + KV-cache write, SwiGLU, plain), for the decoder block of Sec. III-A.
+#include "mfma_common.h"
+#include "mfma_kernels.h"
+
+namespace hyp {
+
+namespace {
+
+// ----------------------------------------------------------------------------
+// Row permutations applied when a weight matrix is repacked, chosen so that the
+// two values an epilogue has to combine land in the same lane and register of
+// two accumulator blocks of one wave (a wave owns 64 packed rows = 2 blocks):
+//   QKV:     inside every head, block 0 of a wave holds d in [ib, ib+32) and
+//            block 1 holds d + 64 -> the RoPE partner (i, i + 64);
+//   gate/up: block 0 holds gate rows f..f+31, block 1 the up rows of the same f.
+// ----------------------------------------------------------------------------
+__device__ inline int src_row_qkv(int r) {  // packed row -> row of [wq; wk; wv]
+  int head = r >> 7, w = (r >> 6) & 1, i = (r >> 5) & 1, x = r & 31;
+  return head * 128 + w * 32 + i * 64 + x;
+}
+__device__ inline int src_row_gateup(int r, int I) {  // packed row -> row of [gate; up]
+  int tile = r >> 8, w = (r >> 6) & 3, i = (r >> 5) & 1, x = r & 31;
+  int f = tile * 128 + w * 32 + x;
+  return i ? I + f : f;
+}
+
+// one thread per 16-byte chunk of the destination
+__global__ void __launch_bounds__(256) k_pack_weight(const bf16_t *__restrict__ src0,
+                                                     const bf16_t *__restrict__ src1,
+                                                     const bf16_t *__restrict__ src2, int rows0,
+                                                     int rows1, bf16_t *__restrict__ dst, int N, int K,
+                                                     int mode, int I) {
+  size_t chunk = (size_t)blockIdx.x * 256 + threadIdx.x;
+  size_t total = (size_t)N * K / 8;
+  if (chunk >= total) return;
+  size_t tile = chunk >> 6;
+  int lane = chunk & 63;
+  int rb = (int)(tile / (K >> 4)), kt = (int)(tile % (K >> 4));
+  int r = rb * 32 + (lane & 31), k = kt * 16 + (lane >> 5) * 8;
+  int sr = mode == PACK_QKV ? src_row_qkv(r) : mode == PACK_GATEUP ? src_row_gateup(r, I) : r;
+  const bf16_t *s;
+  if (sr < rows0) s = src0 + (size_t)sr * K;
+  else if (sr < rows0 + rows1) s = src1 + (size_t)(sr - rows0) * K;
+  else s = src2 + (size_t)(sr - rows0 - rows1) * K;
+  *(u16x8_t *)(dst + chunk * 8) = *(const u16x8_t *)(s + k);
+}
+
+// ----------------------------------------------------------------------------
+// Residual add + RMS Norm over internal rows.
+//   x = (first ? hidden_in[row_ext] : xres) + sum_s delta_s          (fp32)
+//   xres = x;  y = x * rsqrt(mean(x^2) + eps) * g   -> P(rows, H)   (norm mode)
+//   hidden_out[row_ext] = x                                           (final mode)
+// delta is either one fragment-order bf16 matrix P(rows, H) (prefill GEMM
+// output) or n_part fp32 partial sums [n_part][H][32] (decode split-K output,
+// rows = tokens < 32).
+// A 256-thread block owns 8 consecutive rows; thread t works on row t % 8.
+// ----------------------------------------------------------------------------
+template <int MODE>  // 0: norm -> y ; 1: final -> hidden_out
+__global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hidden_in,
+                                                  float *__restrict__ xres,
+                                                  const bf16_t *__restrict__ delta_bf,
+                                                  const float *__restrict__ delta_part, int n_part,
+                                                  size_t part_stride, const bf16_t *__restrict__ gain,
+                                                  bf16_t *__restrict__ y, bf16_t *__restrict__ hidden_out,
+                                                  const int *__restrict__ row_ext, int H, float eps) {
+  __shared__ float red[8][33];
+  int r8 = threadIdx.x & 7, cg = threadIdx.x >> 3;  // cg: 0..31 chunk lane
+  int row = blockIdx.x * 8 + r8;
+  int ext = row_ext[row];
+  int nchunk = H >> 3;
+  float ss = 0.f;
+  float *xr = xres + (size_t)row * H;
+  for (int c = cg; c < nchunk; c += 32) {
+    float v[8];
+    if (ext < 0) {
+      for (int e = 0; e < 8; ++e) v[e] = 0.f;
+    } else {
+      if (hidden_in) {
+        u16x8_t h = *(const u16x8_t *)(hidden_in + (size_t)ext * H + c * 8);
+        for (int e = 0; e < 8; ++e) v[e] = bf16_to_f32(h.v[e]);
+      } else {
+        f32x4_t a = *(const f32x4_t *)(xr + c * 8), b = *(const f32x4_t *)(xr + c * 8 + 4);
+        for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
+      }
+      if (delta_bf) {
+        u16x8_t d = *(const u16x8_t *)(delta_bf + frag_offset(row, c * 8, H));
+        for (int e = 0; e < 8; ++e) v[e] += bf16_to_f32(d.v[e]);
+      }
+      for (int s = 0; s < n_part; ++s) {
+        const float *p = delta_part + s * part_stride + (size_t)(c * 8) * 32 + row;  // [n][32 tokens]
+        for (int e = 0; e < 8; ++e) v[e] += p[e * 32];
+      }
+    }
+    if (MODE == 0) {
+      f32x4_t a, b;
+      for (int e = 0; e < 4; ++e) { a[e] = v[e]; b[e] = v[4 + e]; }
+      *(f32x4_t *)(xr + c * 8) = a;
+      *(f32x4_t *)(xr + c * 8 + 4) = b;
+      for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+    } else if (ext >= 0) {
+      u16x8_t o;
+      for (int e = 0; e < 8; ++e) o.v[e] = f2bf_dev(v[e]);
+      *(u16x8_t *)(hidden_out + (size_t)ext * H + c * 8) = o;
+    }
+  }
+  if (MODE == 1) return;
+  red[r8][cg] = ss;
+  __syncthreads();
+  float tot = 0.f;
+  for (int i = 0; i < 32; ++i) tot += red[r8][i];
+  float rs = 1.0f / sqrtf(tot / (float)H + eps);
+  for (int c = cg; c < nchunk; c += 32) {
+    f32x4_t a = *(const f32x4_t *)(xr + c * 8), b = *(const f32x4_t *)(xr + c * 8 + 4);
+    u16x8_t gg = *(const u16x8_t *)(gain + c * 8);
+    u16x8_t o;
+    for (int e = 0; e < 4; ++e) {
+      o.v[e] = f2bf_dev(a[e] * rs * bf16_to_f32(gg.v[e]));
+      o.v[4 + e] = f2bf_dev(b[e] * rs * bf16_to_f32(gg.v[4 + e]));
+    }
+    *(u16x8_t *)(y + frag_offset(row, c * 8, H)) = o;
+  }
+}
+
+// ----------------------------------------------------------------------------
+// GEMM  C^T[N, T] = W[N, K] X[T, K]^T  on fragment-order operands.
+//
+// Workgroup tile 256 features x 256 tokens, 8 waves (4 along features x 2 along
+// tokens), each wave 2 x 4 accumulator blocks of 32x32 (128 fp32 registers).
+// K advances in stages of 32 (2 k-tiles); 4 stages of 32 KiB rotate through LDS
+// and are filled by direct global->LDS wave loads issued three stages ahead, 4
+// per wave and stage, interleaved with the MFMAs.  Fragments are read from LDS
+// with linear, conflict-free ds_read_b128 one k-tile ahead of the MFMAs that
+// use them.  One barrier per stage.  Workgroups are numbered so that the ones
+// that run together on an XCD (id % 8) cover a band of `gm` token tiles times
+// consecutive feature tiles and share operand panels in that XCD's L2.
+// ----------------------------------------------------------------------------
+constexpr int WF = 4, WT = 2, FB = 2, TB = 4, KTS = 2, NST = 4;
+constexpr int XB = WT * TB, NBK = WF * FB;           // 8 token blocks, 8 feature blocks
+constexpr int STAGE_BYTES = (XB + NBK) * KTS * 1024;  // 32 KiB
+constexpr int LPW = (XB + NBK) * KTS / (WF * WT);     // 4 wave loads per wave and stage
+constexpr int GEMM_LDS = STAGE_BYTES * NST;           // 128 KiB
+
+struct GemmParams {
+  const bf16_t *X;   // P(T', K)
+  const bf16_t *W;   // P(N, K)
+  int KT;            // K / 16
+  int tok_blocks;    // T' / 32
+  int feat_blocks;   // N / 32 (multiple of 8)
+  int gm;            // token tiles per band
+  int n_tiles;
+  // epilogue
+  bf16_t *out;       // EPI_STORE: P(T', N); EPI_SWIGLU: P(T', N/2); EPI_QKV: q as P(T', qd)
+  int out_K;         // row length of `out`
+  bf16_t *Kc, *Vc;   // EPI_QKV: caches of this layer
+  CacheGeom geom;
+  int qd, kvd;
+  const float *cos_tab, *sin_tab;  // [pos][64]
+  const int *row_pos, *row_req;    // per internal row
+};
+
+__device__ __forceinline__ void store_block(bf16_t *out, int out_K, int tb, int f0, int lane,
+                                            const float *v /*16*/) {
+  // 32 features [f0, f0+32) x 32 tokens of block tb into P(T', out_K)
+  int hh = lane >> 5, t = lane & 31;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    size_t off = ((size_t)tb * (out_K >> 4) + ((f0 + 8 * g) >> 4)) * kTileElems + (((g & 1) << 5) + t) * 8 + hh * 4;
+    *(bf16x4_t *)(out + off) = pack4(v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]);
+  }
+}
+
+template <int EPI>
+__global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wf = wave / WT, wt = wave % WT;
+  // tile of this workgroup
+  int nwg = gridDim.x, id = blockIdx.x;
+  int q = (id % 8) * (nwg / 8) + id / 8;
+  if (q >= p.n_tiles) return;
+  const int tiles_n = p.feat_blocks / NBK;
+  const int tiles_t = (p.tok_blocks + XB - 1) / XB;
+  int band = q / (p.gm * tiles_n);
+  int in_band = q - band * p.gm * tiles_n;
+  int rows_in_band = min(p.gm, tiles_t - band * p.gm);
+  int tile_n = in_band / rows_in_band, tile_t = band * p.gm + in_band % rows_in_band;
+  const int tb0 = tile_t * XB, nb0 = tile_n * NBK;
+  const int KT = p.KT;
+
+  f32x16_t acc[FB][TB];
+#pragma unroll
+  for (int i = 0; i < FB; ++i)
+#pragma unroll
+    for (int j = 0; j < TB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nsteps = KT / KTS;  // >= NST guaranteed by the host
+  const bf16_t *src[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    int lid = wave * LPW + i;
+    int blk = lid / KTS, kt = lid % KTS;
+    if (blk >= XB) {
+      src[i] = p.W + ((size_t)(nb0 + blk - XB) * KT + kt) * kTileElems + lane * 8;
+    } else {
+      int tb = min(tb0 + blk, p.tok_blocks - 1);  // tail tile: reread the last block
+      src[i] = p.X + ((size_t)tb * KT + kt) * kTileElems + lane * 8;
+    }
+  }
+  auto issue1 = [&](int i, int step, int buf) {
+    __builtin_amdgcn_global_load_lds((gbl_ptr_t *)(src[i] + (size_t)step * KTS * kTileElems),
+                                     (lds_ptr_t *)(lds + buf * STAGE_BYTES + (wave * LPW + i) * 1024), 16, 0, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < NST; ++s)
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) issue1(i, s, s);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (((NST - 1) * LPW) & 15) | ((((NST - 1) * LPW) >> 4) << 14));
+  __builtin_amdgcn_s_barrier();
+
+  bf16x8_t wfr[2][FB], xfr[2][TB];
+  auto readfr = [&](int which, int buf, int kt) {
+    const char *base = lds + buf * STAGE_BYTES + lane * 16;
+#pragma unroll
+    for (int i = 0; i < FB; ++i) wfr[which][i] = *(const bf16x8_t *)(base + ((XB + wf * FB + i) * KTS + kt) * 1024);
+#pragma unroll
+    for (int i = 0; i < TB; ++i) xfr[which][i] = *(const bf16x8_t *)(base + ((wt * TB + i) * KTS + kt) * 1024);
+  };
+  readfr(0, 0, 0);
+  int buf = 0;
+  for (int s = 0; s + 1 < nsteps; ++s) {
+    int nbuf = buf + 1 == NST ? 0 : buf + 1;
+    int lstep = s + NST < nsteps ? s + NST : nsteps - 1;  // tail refills land in buffers nobody reads again
+#pragma unroll
+    for (int kt = 0; kt < KTS; ++kt) {
+      const int c = kt & 1, n = c ^ 1;
+      if (kt == KTS - 1) {
+        // my part of stage s+1 has landed and all my LDS reads of stage s are done
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0070 | (((NST - 2) * LPW) & 15) | ((((NST - 2) * LPW) >> 4) << 14));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < FB; ++i)
+#pragma unroll
+          for (int j = 0; j < TB; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
+            if (i == 0 && j == 0) {
+              __builtin_amdgcn_sched_barrier(0);
+              readfr(n, nbuf, 0);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            if (((i * TB + j) & 1) == 1 && ((i * TB + j) >> 1) < LPW) issue1((i * TB + j) >> 1, lstep, buf);
+          }
+      } else {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < FB; ++i)
+#pragma unroll
+          for (int j = 0; j < TB; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
+            if (i == 0 && j == 0) {
+              __builtin_amdgcn_sched_barrier(0);
+              readfr(n, buf, kt + 1);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+      }
+    }
+    buf = nbuf;
+  }
+#pragma unroll
+  for (int kt = 0; kt < KTS; ++kt) {
+    const int c = kt & 1, n = c ^ 1;
+    if (kt + 1 < KTS) readfr(n, buf, kt + 1);
+#pragma unroll
+    for (int i = 0; i < FB; ++i)
+#pragma unroll
+      for (int j = 0; j < TB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the tail refills before the wave ends
+
+  // ------------------------------------------------------------------ epilogue
+  const int hh = lane >> 5, tl = lane & 31;
+  if (EPI == EPI_STORE) {
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      int tb = tb0 + wt * TB + j;
+      if (tb >= p.tok_blocks) continue;
+#pragma unroll
+      for (int i = 0; i < FB; ++i) {
+        float v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) v[r] = acc[i][j][r];
+        store_block(p.out, p.out_K, tb, (nb0 + wf * FB + i) * 32, lane, v);
+      }
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    // block 0 = gate, block 1 = up of FFN features [(tile_n*4 + wf)*32, +32)
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      int tb = tb0 + wt * TB + j;
+      if (tb >= p.tok_blocks) continue;
+      float v[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float g = acc[0][j][r], u = acc[1][j][r];
+        v[r] = g / (1.0f + __expf(-g)) * u;
+      }
+      store_block(p.out, p.out_K, tb, (tile_n * 4 + wf) * 32, lane, v);
+    }
+  } else {  // EPI_QKV
+    const int n0 = tile_n * 256;              // first packed row of this tile
+    const int head_in_tile = wf >> 1, ib = (wf & 1) * 32;
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      int tb = tb0 + wt * TB + j;
+      if (tb >= p.tok_blocks) continue;
+      int row = tb * 32 + tl;
+      int pos = p.row_pos[row], req = p.row_req[row];
+      if (n0 < p.qd + p.kvd) {
+        // q or k: rotate the pair (d, d + 64) by the angle of this position
+        float lo[16], hi[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4_t c4 = *(const f32x4_t *)(p.cos_tab + (size_t)pos * 64 + ib + 8 * g + 4 * hh);
+          f32x4_t s4 = *(const f32x4_t *)(p.sin_tab + (size_t)pos * 64 + ib + 8 * g + 4 * hh);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float a = acc[0][j][4 * g + e], b = acc[1][j][4 * g + e];
+            lo[4 * g + e] = a * c4[e] - b * s4[e];
+            hi[4 * g + e] = b * c4[e] + a * s4[e];
+          }
+        }
+        if (n0 < p.qd) {
+          int head = (n0 >> 7) + head_in_tile;
+          store_block(p.out, p.out_K, tb, head * 128 + ib, lane, lo);
+          store_block(p.out, p.out_K, tb, head * 128 + 64 + ib, lane, hi);
+        } else {
+          int kvh = ((n0 - p.qd) >> 7) + head_in_tile;
+          bf16_t *kb = p.Kc + p.geom.off(req, kvh, pos >> 5);  // P(32, 128) of this key block
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            size_t o0 = (size_t)((ib + 8 * g) >> 4) * kTileElems + (((g & 1) << 5) + (pos & 31)) * 8 + hh * 4;
+            size_t o1 = (size_t)((64 + ib + 8 * g) >> 4) * kTileElems + (((g & 1) << 5) + (pos & 31)) * 8 + hh * 4;
+            *(bf16x4_t *)(kb + o0) = pack4(lo[4 * g], lo[4 * g + 1], lo[4 * g + 2], lo[4 * g + 3]);
+            *(bf16x4_t *)(kb + o1) = pack4(hi[4 * g], hi[4 * g + 1], hi[4 * g + 2], hi[4 * g + 3]);
+          }
+        }
+      } else {
+        // v: feature d of kv head, key `pos` -> value tile slot
+        int kvh = ((n0 - p.qd - p.kvd) >> 7) + head_in_tile;
+        bf16_t *vb = p.Vc + p.geom.off(req, kvh, pos >> 5);
+        int m, khh;
+        int e = vtile_slot_of_key(pos & 31, &m, &khh);
+#pragma unroll
+        for (int i = 0; i < FB; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            int d = ib + i * 64 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            vb[(size_t)(m * 4 + (d >> 5)) * kTileElems + (khh * 32 + (d & 31)) * 8 + e] = f2bf_dev(acc[i][j][r]);
+          }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------------------
+// host launchers
+// ----------------------------------------------------------------------------
+hipError_t mfma_pack_weight(const bf16_t *src0, const bf16_t *src1, const bf16_t *src2, int rows0,
+                            int rows1, bf16_t *dst, int N, int K, int mode, int I, hipStream_t s) {
+  size_t chunks = (size_t)N * K / 8;
+  k_pack_weight<<<(unsigned)((chunks + 255) / 256), 256, 0, s>>>(src0, src1, src2, rows0, rows1, dst, N, K, mode, I);
+  return hipGetLastError();
+}
+
+hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *delta_bf,
+                         const float *delta_part, int n_part, size_t part_stride, const bf16_t *gain,
+                         bf16_t *y, bf16_t *hidden_out, const int *row_ext, int rows, int H, float eps,
+                         bool final_mode, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  if (final_mode)
+    k_add_norm<1><<<rows / 8, 256, 0, s>>>(hidden_in, xres, delta_bf, delta_part, n_part, part_stride, gain, y, hidden_out, row_ext, H, eps);
+  else
+    k_add_norm<0><<<rows / 8, 256, 0, s>>>(hidden_in, xres, delta_bf, delta_part, n_part, part_stride, gain, y, hidden_out, row_ext, H, eps);
+  return hipGetLastError();
+}
+
+hipError_t mfma_gemm_init() {
+  hipError_t e = hipFuncSetAttribute((const void *)k_gemm<EPI_STORE>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_QKV>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+  return e;
+}
+
+hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
+                     int out_K, const QkvEpilogue *qkv, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  GemmParams p = {};
+  p.X = X; p.W = W; p.KT = K / 16; p.tok_blocks = rows / 32; p.feat_blocks = N / 32;
+  int tiles_t = (p.tok_blocks + XB - 1) / XB, tiles_n = p.feat_blocks / NBK;
+  p.gm = tiles_t < 8 ? tiles_t : 8;
+  p.n_tiles = tiles_t * tiles_n;
+  p.out = out; p.out_K = out_K;
+  if (qkv) {
+    p.Kc = qkv->Kc; p.Vc = qkv->Vc; p.geom = qkv->geom; p.qd = qkv->qd; p.kvd = qkv->kvd;
+    p.cos_tab = qkv->cos_tab; p.sin_tab = qkv->sin_tab; p.row_pos = qkv->row_pos; p.row_req = qkv->row_req;
+  }
+  int grid = (p.n_tiles + 7) / 8 * 8;
+  if (epi == EPI_STORE) k_gemm<EPI_STORE><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
+  else if (epi == EPI_SWIGLU) k_gemm<EPI_SWIGLU><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
+  else k_gemm<EPI_QKV><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
+  return hipGetLastError();
+}
+
+}  // namespace hyp

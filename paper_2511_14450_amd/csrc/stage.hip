@@ -5,11 +5,13 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <string>
 #include <vector>
 
 #include "common.h"
+#include "mfma_kernels.h"
 
 using namespace hyp;
 
@@ -27,12 +29,36 @@ struct LayerPtrs {
 // Where everything lives inside the caller's workspace.
 struct Layout {
   std::vector<LayerPtrs> layers;
-  size_t Kc, Vc, kv_layer_stride;  // per-layer stride in bytes
-  size_t cos_tab, sin_tab;
-  size_t xres, y, qkv, attn, gu, m;
-  size_t tok_req, tok_pos, lens, iota;
-  size_t total;
+  size_t Kc = 0, Vc = 0, kv_layer_stride = 0;  // per-layer stride in bytes
+  size_t cos_tab = 0, sin_tab = 0;
+  size_t xres = 0, y = 0, qkv = 0, attn = 0, gu = 0, m = 0;
+  size_t tok_req = 0, tok_pos = 0, lens = 0, iota = 0;
+  // MFMA path only
+  size_t q = 0, delta = 0, row_ext = 0, row_pos = 0, row_req = 0, tiles = 0, req_len = 0, row_ext_dec = 0, qdec = 0,
+         partial = 0, attn_part = 0;
+  size_t kv_bytes = 0;  // bytes of each of Kc, Vc over all layers
+  int rows_cap = 0;     // internal rows the scratch holds
+  int key_blocks = 0;   // 32-key blocks per (request, kv head)
+  int max_chunks = 0;   // decode attention chunks per head
+  int ks_qkv = 1, ks_o = 1, ks_gu = 1, ks_d = 1;
+  size_t total = 0;
 };
+
+// The MFMA kernels cover bf16 stages shaped like the models of Table I: head_dim
+// 128, at most 4 query heads per KV head, even head counts and widths that tile
+// by 256; at most 32 resident requests (one token block per decode step).
+bool mfma_applies(const hyp_stage_config_t &c) {
+  if (c.dtype != HYP_BF16 || (c.flags & HYP_FLAG_PLAIN_KERNELS)) return false;
+  if (c.head_dim != 128) return false;
+  int G = c.n_q_heads / c.n_kv_heads;
+  if (G > 4) return false;
+  if (c.n_q_heads % 2 || c.n_kv_heads % 2) return false;
+  if (c.hidden % 256 || c.ffn_dim % 256) return false;
+  if (c.max_batch > 32) return false;
+  return true;
+}
+
+int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
 size_t elem_size(const hyp_stage_config_t &c) { return c.dtype == HYP_BF16 ? 2 : 4; }
 
@@ -76,6 +102,45 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     p.g2 = take(es * H);
     p.wgu = take(es * 2 * I * H);
     p.wd = take(es * H * I);
+  }
+  if (mfma_applies(c)) {
+    // every request's rows are padded to a multiple of 64 (one query tile)
+    L.rows_cap = round_up((int)c.max_prefill_tokens + 63 * c.max_batch, 64);
+    if (L.rows_cap < 64) L.rows_cap = 64;
+    R = L.rows_cap;
+    L.key_blocks = round_up(c.max_seq, 64) / 32;
+    L.kv_layer_stride = align_up(es * (size_t)c.max_batch * c.n_kv_heads * L.key_blocks * 32 * 128);
+    L.kv_bytes = L.kv_layer_stride * n_layers;
+    L.Kc = take(L.kv_bytes);
+    L.Vc = take(L.kv_bytes);
+    size_t tab = sizeof(float) * (size_t)L.key_blocks * 32 * 64;
+    L.cos_tab = take(tab);
+    L.sin_tab = take(tab);
+    L.xres = take(sizeof(float) * R * H);
+    L.y = take(es * R * H);
+    L.q = take(es * R * qd);
+    L.attn = take(es * R * qd);
+    L.m = take(es * R * I);
+    L.delta = take(es * R * H);
+    L.row_ext = take(sizeof(int) * R);
+    L.row_pos = take(sizeof(int) * R);
+    L.row_req = take(sizeof(int) * R);
+    L.tiles = take(sizeof(PrefillTile) * (R / 64));
+    L.req_len = take(sizeof(int) * c.max_batch);
+    L.lens = take(sizeof(int) * c.max_batch);
+    L.row_ext_dec = take(sizeof(int) * 32);
+    L.qdec = take(es * (size_t)c.max_batch * c.n_kv_heads * 32 * 128);
+    L.ks_qkv = mfma_gemv_ksplit((int)(qd + 2 * kvd), (int)H);
+    L.ks_o = mfma_gemv_ksplit((int)H, (int)qd);
+    L.ks_gu = mfma_gemv_ksplit((int)(2 * I), (int)H);
+    L.ks_d = mfma_gemv_ksplit((int)H, (int)I);
+    size_t pf = std::max(std::max((size_t)L.ks_qkv * (qd + 2 * kvd), (size_t)L.ks_o * H),
+                         std::max((size_t)L.ks_gu * 2 * I, (size_t)L.ks_d * H));
+    L.partial = take(sizeof(float) * pf * 32);
+    L.max_chunks = (c.max_seq + kDecodeChunkKeys - 1) / kDecodeChunkKeys;
+    L.attn_part = take(sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks));
+    L.total = off;
+    return;
   }
   L.kv_layer_stride = align_up(es * (size_t)c.max_batch * kvd * c.max_seq);
   L.Kc = take(L.kv_layer_stride * n_layers);
@@ -162,6 +227,119 @@ hyp_status_t copy_weights(hyp_stage *st, const hyp_layer_weights_t *layers) {
   return HYP_OK;
 }
 
+// MFMA path: repack every matrix into fragment order (with the row permutations
+// its epilogue relies on); gains are copied as they are.
+hyp_status_t pack_weights_mfma(hyp_stage *st, const hyp_layer_weights_t *layers) {
+  const Dims &d = st->dm;
+  hipStream_t s = st->stream;
+  for (int l = 0; l < st->n_layers; ++l) {
+    const hyp_layer_weights_t &w = layers[l];
+    const void *ptrs[] = {w.attn_norm_g, w.wq, w.wk, w.wv, w.wo, w.ffn_norm_g, w.w_gate, w.w_up, w.w_down};
+    for (const void *p : ptrs)
+      if (!p) return fail(st, HYP_EINVAL, "a weight pointer of layer " + std::to_string(l) + " is NULL");
+    const LayerPtrs &p = st->L.layers[l];
+    HIP_TRY(st, hipMemcpyAsync(st->ws + p.g1, w.attn_norm_g, 2 * (size_t)d.H, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + p.g2, w.ffn_norm_g, 2 * (size_t)d.H, hipMemcpyDeviceToDevice, s));
+    HIP_TRY(st, mfma_pack_weight((const bf16_t *)w.wq, (const bf16_t *)w.wk, (const bf16_t *)w.wv, d.qd, d.kvd,
+                                 at<bf16_t>(st, p.wqkv), d.qd + 2 * d.kvd, d.H, PACK_QKV, 0, s));
+    HIP_TRY(st, mfma_pack_weight((const bf16_t *)w.wo, nullptr, nullptr, d.H, 0, at<bf16_t>(st, p.wo), d.H, d.qd,
+                                 PACK_PLAIN, 0, s));
+    HIP_TRY(st, mfma_pack_weight((const bf16_t *)w.w_gate, (const bf16_t *)w.w_up, nullptr, d.I, d.I,
+                                 at<bf16_t>(st, p.wgu), 2 * d.I, d.H, PACK_GATEUP, d.I, s));
+    HIP_TRY(st, mfma_pack_weight((const bf16_t *)w.w_down, nullptr, nullptr, d.H, 0, at<bf16_t>(st, p.wd), d.H, d.I,
+                                 PACK_PLAIN, 0, s));
+  }
+  // Cache blocks are read 32 keys at a time; slots that were never written must
+  // hold finite numbers because a masked probability of 0 still multiplies them.
+  HIP_TRY(st, mfma_fill_zero(st->ws + st->L.Kc, st->L.kv_bytes, s));
+  HIP_TRY(st, mfma_fill_zero(st->ws + st->L.Vc, st->L.kv_bytes, s));
+  HIP_TRY(st, mfma_fill_zero(st->ws + st->L.qdec, 2 * (size_t)d.max_batch * d.nkv * 32 * 128, s));
+  return HYP_OK;
+}
+
+CacheGeom cache_geom(const hyp_stage *st) {
+  CacheGeom g;
+  g.nkv = st->dm.nkv;
+  g.key_blocks = st->L.key_blocks;
+  return g;
+}
+
+// prefill through the MFMA kernels; `rows` internal rows (multiple of 64)
+hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden_out, int rows, int n_tiles) {
+  const Dims &d = st->dm;
+  hipStream_t s = st->stream;
+  const Layout &L = st->L;
+  float *xres = at<float>(st, L.xres);
+  bf16_t *y = at<bf16_t>(st, L.y), *q = at<bf16_t>(st, L.q), *attn = at<bf16_t>(st, L.attn);
+  bf16_t *m = at<bf16_t>(st, L.m), *delta = at<bf16_t>(st, L.delta);
+  const int *row_ext = at<int>(st, L.row_ext);
+  CacheGeom geom = cache_geom(st);
+  HIP_TRY(st, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
+                            nullptr, row_ext, rows, d.H, d.eps, false, s));
+  for (int l = 0; l < st->n_layers; ++l) {
+    const LayerPtrs &p = L.layers[l];
+    QkvEpilogue e;
+    e.Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l);
+    e.Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
+    e.geom = geom; e.qd = d.qd; e.kvd = d.kvd;
+    e.cos_tab = at<float>(st, L.cos_tab); e.sin_tab = at<float>(st, L.sin_tab);
+    e.row_pos = at<int>(st, L.row_pos); e.row_req = at<int>(st, L.row_req);
+    HIP_TRY(st, mfma_gemm(EPI_QKV, y, at<bf16_t>(st, p.wqkv), rows, d.qd + 2 * d.kvd, d.H, q, d.qd, &e, s));
+    HIP_TRY(st, mfma_attn_prefill(q, e.Kc, e.Vc, geom, attn, at<PrefillTile>(st, L.tiles), n_tiles,
+                                  at<int>(st, L.req_len), d.nq, d.nkv, s));
+    HIP_TRY(st, mfma_gemm(EPI_STORE, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, delta, d.H, nullptr, s));
+    HIP_TRY(st, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, p.g2), y, nullptr, row_ext, rows, d.H,
+                              d.eps, false, s));
+    HIP_TRY(st, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, nullptr, s));
+    HIP_TRY(st, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, nullptr, s));
+    if (l + 1 < st->n_layers)
+      HIP_TRY(st, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, L.layers[l + 1].g1), y, nullptr,
+                                row_ext, rows, d.H, d.eps, false, s));
+    else
+      HIP_TRY(st, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, nullptr, nullptr, (bf16_t *)hidden_out, row_ext, rows,
+                                d.H, d.eps, true, s));
+  }
+  return HYP_OK;
+}
+
+// one decode step through the MFMA kernels: a single block of 32 token rows
+hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_out) {
+  const Dims &d = st->dm;
+  hipStream_t s = st->stream;
+  const Layout &L = st->L;
+  const int B = st->batch;
+  float *xres = at<float>(st, L.xres), *part = at<float>(st, L.partial);
+  bf16_t *y = at<bf16_t>(st, L.y), *attn = at<bf16_t>(st, L.attn), *m = at<bf16_t>(st, L.m);
+  bf16_t *qdec = at<bf16_t>(st, L.qdec);
+  const int *row_ext = at<int>(st, L.row_ext_dec), *lens = at<int>(st, L.lens);
+  const float *ct = at<float>(st, L.cos_tab), *sn = at<float>(st, L.sin_tab);
+  CacheGeom geom = cache_geom(st);
+  const int Nqkv = d.qd + 2 * d.kvd;
+  HIP_TRY(st, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
+                            nullptr, row_ext, 32, d.H, d.eps, false, s));
+  for (int l = 0; l < st->n_layers; ++l) {
+    const LayerPtrs &p = L.layers[l];
+    bf16_t *Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l), *Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
+    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wqkv), y, part, Nqkv, d.H, L.ks_qkv, B, s));
+    HIP_TRY(st, mfma_dec_qkv_finish(part, L.ks_qkv, Nqkv, lens, ct, sn, qdec, Kc, Vc, geom, d.nq, d.nkv, B, s));
+    HIP_TRY(st, mfma_attn_decode(qdec, Kc, Vc, geom, lens, at<float>(st, L.attn_part), attn, d.nq, d.nkv, B,
+                                 L.max_chunks, s));
+    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wo), attn, part, d.H, d.qd, L.ks_o, B, s));
+    HIP_TRY(st, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_o, (size_t)d.H * 32, at<bf16_t>(st, p.g2), y, nullptr,
+                              row_ext, 32, d.H, d.eps, false, s));
+    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wgu), y, part, 2 * d.I, d.H, L.ks_gu, B, s));
+    HIP_TRY(st, mfma_dec_swiglu(part, L.ks_gu, d.I, m, B, s));
+    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wd), m, part, d.H, d.I, L.ks_d, B, s));
+    if (l + 1 < st->n_layers)
+      HIP_TRY(st, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, at<bf16_t>(st, L.layers[l + 1].g1),
+                                y, nullptr, row_ext, 32, d.H, d.eps, false, s));
+    else
+      HIP_TRY(st, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, nullptr, nullptr,
+                                (bf16_t *)hidden_out, row_ext, 32, d.H, d.eps, true, s));
+  }
+  return HYP_OK;
+}
+
 // rows tokens through every block with the shape-generic kernels
 template <typename T>
 hyp_status_t run_plain(hyp_stage *st, const void *hidden_in, void *hidden_out, int rows,
@@ -227,7 +405,7 @@ hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_
   st->l_start = l_start; st->l_end = l_end; st->n_layers = l_end - l_start;
   st->stream = (hipStream_t)hip_stream;
   st->bf16 = cfg->dtype == HYP_BF16;
-  st->mfma = false;
+  st->mfma = mfma_applies(*cfg);
   st->ws = (char *)workspace;
   st->h_stage = nullptr; st->upload_done = nullptr; st->upload_pending = false;
   st->batch = 0; st->prefilled = false;
@@ -250,7 +428,8 @@ hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_
     return code;
   };
 
-  st->h_stage_ints = 2 * (size_t)max_rows(*cfg) + 2 * (size_t)cfg->max_batch;
+  st->h_stage_ints = st->mfma ? 3 * (size_t)st->L.rows_cap + 3 * ((size_t)st->L.rows_cap / 64) + 2 * (size_t)cfg->max_batch + 32
+                              : 2 * (size_t)max_rows(*cfg) + 2 * (size_t)cfg->max_batch;
   if (hipHostMalloc((void **)&st->h_stage, sizeof(int) * st->h_stage_ints, hipHostMallocDefault) != hipSuccess) {
     st->h_stage = nullptr; st->err = "hipHostMalloc failed";
     return bail(HYP_ENOMEM);
@@ -260,16 +439,24 @@ hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_
     return bail(HYP_EDEVICE);
   }
 
-  rc = copy_weights(st, layers);
+  if (st->mfma) {
+    hipError_t e = mfma_gemm_init();
+    if (e == hipSuccess) e = mfma_gemv_init();
+    if (e != hipSuccess) { st->err = std::string("kernel attributes: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
+    rc = pack_weights_mfma(st, layers);
+  } else {
+    rc = copy_weights(st, layers);
+  }
   if (rc != HYP_OK) return bail(rc);
 
   // RoPE tables: angle = pos * base^(-2i/d), formed in double on the host
   {
     int half = d.d / 2;
-    std::vector<float> ct((size_t)d.max_seq * half), sn((size_t)d.max_seq * half);
+    int n_pos = st->mfma ? st->L.key_blocks * 32 : d.max_seq;  // the MFMA path also rotates padding rows
+    std::vector<float> ct((size_t)n_pos * half), sn((size_t)n_pos * half);
     for (int i = 0; i < half; ++i) {
       double theta = pow((double)cfg->rope_base, -2.0 * (double)i / (double)d.d);
-      for (int p = 0; p < d.max_seq; ++p) {
+      for (int p = 0; p < n_pos; ++p) {
         double a = (double)p * theta;
         ct[(size_t)p * half + i] = (float)cos(a);
         sn[(size_t)p * half + i] = (float)sin(a);
@@ -280,7 +467,7 @@ hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_
       e = hipMemcpyAsync(st->ws + st->L.sin_tab, sn.data(), sizeof(float) * sn.size(), hipMemcpyHostToDevice, st->stream);
     std::vector<int> iota(cfg->max_batch);
     for (int i = 0; i < cfg->max_batch; ++i) iota[i] = i;
-    if (e == hipSuccess)
+    if (e == hipSuccess && !st->mfma)
       e = hipMemcpyAsync(st->ws + st->L.iota, iota.data(), sizeof(int) * iota.size(), hipMemcpyHostToDevice, st->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(st->stream);  // host vectors die here
     if (e != hipSuccess) { st->err = std::string("table upload: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
@@ -305,23 +492,56 @@ hyp_status_t stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t
 
   hyp_status_t rc = wait_upload(st);
   if (rc != HYP_OK) return rc;
-  int *h_req = st->h_stage, *h_pos = st->h_stage + rows, *h_len = st->h_stage + 2 * (size_t)rows;
-  {
-    int t = 0;
-    for (int b = 0; b < batch; ++b)
-      for (int p = 0; p < seq_lens[b]; ++p, ++t) { h_req[t] = b; h_pos[t] = p; }
-    for (int b = 0; b < batch; ++b) h_len[b] = seq_lens[b];
-  }
   hipStream_t s = st->stream;
-  HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.tok_req, h_req, sizeof(int) * rows, hipMemcpyHostToDevice, s));
-  HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.tok_pos, h_pos, sizeof(int) * rows, hipMemcpyHostToDevice, s));
-  HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.lens, h_len, sizeof(int) * batch, hipMemcpyHostToDevice, s));
-  HIP_TRY(st, hipEventRecord(st->upload_done, s));
-  st->upload_pending = true;
-
-  const int *tok_req = at<int>(st, st->L.tok_req), *tok_pos = at<int>(st, st->L.tok_pos);
-  rc = st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, rows, tok_req, tok_pos)
-                : run_plain<float>(st, hidden_in, hidden_out, rows, tok_req, tok_pos);
+  if (st->mfma) {
+    // internal rows: every request starts at a multiple of 64 and is padded to one
+    const Layout &L = st->L;
+    int R = 0;
+    for (int b = 0; b < batch; ++b) R += round_up(seq_lens[b], 64);
+    int *h_ext = st->h_stage, *h_pos = h_ext + R, *h_req = h_pos + R;
+    PrefillTile *h_tiles = (PrefillTile *)(h_req + R);
+    int n_tiles = R / 64;
+    int *h_len = (int *)(h_tiles + n_tiles), *h_ext_dec = h_len + batch;
+    int row = 0, ext = 0, nt = 0;
+    for (int b = 0; b < batch; ++b) {
+      int padded = round_up(seq_lens[b], 64);
+      for (int p = 0; p < padded; ++p, ++row) {
+        h_ext[row] = p < seq_lens[b] ? ext + p : -1;
+        h_pos[row] = p;
+        h_req[row] = b;
+      }
+      for (int qb = 0; qb < padded / 32; qb += 2) h_tiles[nt++] = PrefillTile{b, row - padded + qb * 32, qb};
+      ext += seq_lens[b];
+      h_len[b] = seq_lens[b];
+    }
+    for (int i = 0; i < 32; ++i) h_ext_dec[i] = i < batch ? i : -1;
+    HIP_TRY(st, hipMemcpyAsync(st->ws + L.row_ext, h_ext, sizeof(int) * R, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + L.row_pos, h_pos, sizeof(int) * R, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + L.row_req, h_req, sizeof(int) * R, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + L.tiles, h_tiles, sizeof(PrefillTile) * n_tiles, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + L.req_len, h_len, sizeof(int) * batch, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + L.lens, h_len, sizeof(int) * batch, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + L.row_ext_dec, h_ext_dec, sizeof(int) * 32, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipEventRecord(st->upload_done, s));
+    st->upload_pending = true;
+    rc = run_prefill_mfma(st, hidden_in, hidden_out, R, n_tiles);
+  } else {
+    int *h_req = st->h_stage, *h_pos = st->h_stage + rows, *h_len = st->h_stage + 2 * (size_t)rows;
+    {
+      int t = 0;
+      for (int b = 0; b < batch; ++b)
+        for (int p = 0; p < seq_lens[b]; ++p, ++t) { h_req[t] = b; h_pos[t] = p; }
+      for (int b = 0; b < batch; ++b) h_len[b] = seq_lens[b];
+    }
+    HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.tok_req, h_req, sizeof(int) * rows, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.tok_pos, h_pos, sizeof(int) * rows, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.lens, h_len, sizeof(int) * batch, hipMemcpyHostToDevice, s));
+    HIP_TRY(st, hipEventRecord(st->upload_done, s));
+    st->upload_pending = true;
+    const int *tok_req = at<int>(st, st->L.tok_req), *tok_pos = at<int>(st, st->L.tok_pos);
+    rc = st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, rows, tok_req, tok_pos)
+                  : run_plain<float>(st, hidden_in, hidden_out, rows, tok_req, tok_pos);
+  }
   if (rc != HYP_OK) return rc;
   st->lens.assign(seq_lens, seq_lens + batch);
   st->batch = batch;
@@ -337,8 +557,9 @@ hyp_status_t stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hid
     if (st->lens[b] >= st->cfg.max_seq)
       return fail(st, HYP_ECAPACITY, "request " + std::to_string(b) + " already holds max_seq tokens");
   const int *iota = at<int>(st, st->L.iota), *lens = at<int>(st, st->L.lens);
-  hyp_status_t rc = st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, st->batch, iota, lens)
-                             : run_plain<float>(st, hidden_in, hidden_out, st->batch, iota, lens);
+  hyp_status_t rc = st->mfma   ? run_decode_mfma(st, hidden_in, hidden_out)
+                    : st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, st->batch, iota, lens)
+                               : run_plain<float>(st, hidden_in, hidden_out, st->batch, iota, lens);
   if (rc != HYP_OK) return rc;
   HIP_TRY(st, advance_lens(at<int>(st, st->L.lens), st->batch, st->stream));
   for (int b = 0; b < st->batch; ++b) st->lens[b] += 1;
@@ -352,7 +573,10 @@ hyp_status_t stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, vo
   if (!st->prefilled || request < 0 || request >= st->batch) return fail(st, HYP_ESTATE, "no such request");
   size_t off = st->L.kv_layer_stride * layer;
   int len = st->lens[request];
-  if (st->bf16)
+  if (st->mfma)
+    HIP_TRY(st, mfma_export_kv(at<bf16_t>(st, st->L.Kc + off), at<bf16_t>(st, st->L.Vc + off), cache_geom(st),
+                               (bf16_t *)k_out, (bf16_t *)v_out, request, len, st->dm.nkv, st->stream));
+  else if (st->bf16)
     HIP_TRY(st, plain_export_kv<bf16_t>(at<bf16_t>(st, st->L.Kc + off), at<bf16_t>(st, st->L.Vc + off),
                                         (bf16_t *)k_out, (bf16_t *)v_out, request, len, st->dm, st->stream));
   else

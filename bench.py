@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Throughput of one pipeline stage on one MI355X.
+
+A *step* is one pass of the whole stage hot path over one synthetic batch:
+stage_prefill over the prompts, then the workload's KV-cached stage_decode_step
+calls.  Default workload: c3_stage10 = 10 Phi-3-medium-shaped blocks (a quarter
+of the 40 of Table I), prefill 8 x 2048, then 128 decode steps at batch 8.
+
+Prints ONE JSON line: whole-step tokens/s (prefill and decode tokens together,
+with the two phases also given separately), the roofline of the kernel class
+that takes the most time (durations from HIP events recorded by the library
+around every launch of that class), and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from workloads import synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4096 FLOP/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def device_weights(shape, n_layers, seed):
+    """Seeded N(0, 0.02^2) matrices and 1 + N(0, 0.02^2) gains, drawn on the device
+    (10-20 layers of 341 M parameters each are too slow to draw on the host)."""
+    import torch
+    gen = torch.Generator(device="cuda")
+    layers = []
+    for l in range(n_layers):
+        w = {}
+        for t, (name, shp) in enumerate(shape.weight_shapes().items()):
+            gen.manual_seed(seed * 1000 + (l + 1) * 16 + t)
+            z = torch.randn(shp, generator=gen, device="cuda", dtype=torch.float32) * 0.02
+            if name.endswith("_g"):
+                z += 1.0
+            w[name] = z.to(torch.bfloat16).contiguous()
+        layers.append(w)
+    return layers
+
+
+def device_normal(shape, seed):
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    return torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16).contiguous()
+
+
+def cpu_baseline(wl, prompt=384, decode=8):
+    """The oracle as it stands on a bounded sample: ONE block of the workload's
+    shape over one request of `prompt` tokens plus `decode` cached steps.  Its
+    tokens/s is divided by the stage's block count to be comparable with `value`."""
+    from oracle import hyp_oracle as orc
+    shape = wl.shape
+    w = synth.layer_weights(shape, 0, wl.seed)
+    x = synth.hidden_states(prompt + decode, shape, wl.seed + 1)
+    st = orc.Stage(shape, [w], 1, prompt + decode, "f32")
+    t0 = time.perf_counter()
+    st.prefill(x[:prompt], [prompt])
+    for i in range(decode):
+        st.decode_step(x[prompt + i: prompt + i + 1])
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": (prompt + decode) / dt / wl.n_layers,
+        "unit": "tokens/s",
+        "cores": cores,
+        "kind": "oracle",
+        "seconds": dt,
+        "sample": f"1 of {wl.n_layers} blocks, 1 request: {prompt} prompt tokens + {decode} cached decode steps; "
+                  f"tokens/s divided by {wl.n_layers} blocks",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c3_stage10", choices=[k for k in synth.WORKLOADS if k != "c1_tiny_f32"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one stage on ONE GPU: a stage is the unit the pipeline places on a single "
+              "device, and this build has no multi-GPU path. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_14450_amd as hyp
+
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    wl = synth.WORKLOADS[args.workload]
+    shape = wl.shape
+    lens = wl.lengths()
+    B, T = len(lens), sum(lens)
+    n_dec = wl.decode_steps
+    cfg = hyp.stage_config(shape, B, max(lens) + n_dec, T)
+    layers = device_weights(shape, wl.n_layers, wl.seed)
+    stage = hyp.stage_create(cfg, 0, wl.n_layers, layers)
+    del layers
+    torch.cuda.empty_cache()
+    assert stage.uses_mfma(), "the bench workload must run on the MFMA path"
+
+    x = device_normal((T, shape.hidden), wl.seed + 1)
+    xd = device_normal((max(n_dec, 1), B, shape.hidden), wl.seed + 2)
+    y = torch.empty_like(x)
+    yd = torch.empty((B, shape.hidden), dtype=torch.bfloat16, device="cuda")
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    pre_ms, dec_ms = [], []
+
+    def step(record):
+        if record:
+            ev[0].record()
+        stage.prefill(x, lens, y)
+        if record:
+            ev[1].record()
+        for s in range(n_dec):
+            stage.decode_step(xd[s], yd)
+        if record:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+        torch.cuda.synchronize()
+        pre_ms.append(ev[0].elapsed_time(ev[1]))
+        dec_ms.append(ev[1].elapsed_time(ev[2]))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    tokens_per_step = T + B * n_dec
+    pre = float(np.median(pre_ms))
+    dec = float(np.median(dec_ms))
+
+    # per-kernel-class durations: one extra step with events around every launch
+    H, I, qd, kvd = shape.hidden, shape.ffn_dim, shape.q_dim, shape.kv_dim
+    ctx_mean = float(np.mean(lens)) + (n_dec - 1) / 2.0 + 1
+    gemm_flops = {"gemm_qkv": 2.0 * T * (qd + 2 * kvd) * H, "gemm_o": 2.0 * T * H * qd,
+                  "gemm_gateup": 2.0 * T * 2 * I * H, "gemm_down": 2.0 * T * H * I,
+                  "attn_prefill": sum(2.0 * 2 * shape.n_q_heads * shape.head_dim * L * (L + 1) / 2 for L in lens)}
+    gemv_bytes = {"gemv_qkv": 2.0 * (qd + 2 * kvd) * H, "gemv_o": 2.0 * H * qd, "gemv_gateup": 2.0 * 2 * I * H,
+                  "gemv_down": 2.0 * H * I, "attn_decode": 2.0 * 2 * kvd * B * ctx_mean}
+    classes = list(gemm_flops) + (list(gemv_bytes) if n_dec else [])
+    stage.profile(classes)
+    step(False)
+    rows = []
+    for c in classes:
+        ms, n = stage.profile_read(c)
+        if n == 0:
+            continue
+        avg_s = ms / n * 1e-3
+        if c in gemm_flops:
+            ach = gemm_flops[c] / avg_s / 1e12
+            rows.append({"kernel": c, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                         "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "launches": n, "avg_ms": ms / n, "total_ms": ms})
+        else:
+            ach = gemv_bytes[c] / avg_s / 1e9
+            rows.append({"kernel": c, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": ach / PEAK_HBM_GBS, "traffic": None, "launches": n, "avg_ms": ms / n, "total_ms": ms})
+    stage.profile([])
+    rows.sort(key=lambda r: -r["total_ms"])
+    dominant = rows[0]
+
+    out = {
+        "metric": "stage tokens/sec (prefill & decode) per MI355X",
+        "value": tokens_per_step / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.n_layers, "batch": B, "prefill_tokens": T,
+                   "decode_steps": n_dec, "hidden": H, "ffn": I, "q_heads": shape.n_q_heads,
+                   "kv_heads": shape.n_kv_heads},
+        "prefill_tokens_per_s": T / (pre * 1e-3),
+        "decode_tokens_per_s": (B * n_dec / (dec * 1e-3)) if n_dec else None,
+        "prefill_ms": pre, "decode_ms_per_step": dec / n_dec if n_dec else None,
+        "prefill_gemm_frac_of_mfma_peak": sum(gemm_flops[k] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down"))
+        * wl.n_layers / (pre * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "decode_frac_of_hbm_peak": (wl.n_layers * sum(gemv_bytes.values()) / (dec / n_dec * 1e-3) / 1e9 / PEAK_HBM_GBS)
+        if n_dec else None,
+        "roofline": {k: dominant[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "kernels": rows,
+    }
+    if not args.no_cpu_baseline:
+        stage.destroy()
+        del stage
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

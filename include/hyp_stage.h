@@ -161,6 +161,35 @@ HYP_API hyp_status_t stage_destroy(hyp_stage_t *stage);
  * the library, valid until the next call; never NULL. */
 HYP_API const char *stage_last_error(const hyp_stage_t *stage);
 
+/* Kernel classes of the MFMA path, for stage_profile(). */
+typedef enum {
+  HYP_K_ADD_NORM = 0,       /* residual add + RMS Norm (prefill and decode)        */
+  HYP_K_GEMM_QKV = 1,       /* prefill QKV projection + RoPE + cache write         */
+  HYP_K_ATTN_PREFILL = 2,   /* causal GQA attention over the prompt                */
+  HYP_K_GEMM_O = 3,         /* prefill attention output projection                 */
+  HYP_K_GEMM_GATEUP = 4,    /* prefill gate/up projection + SwiGLU                 */
+  HYP_K_GEMM_DOWN = 5,      /* prefill down projection                             */
+  HYP_K_GEMV_QKV = 6,       /* decode QKV projection (weight streaming)            */
+  HYP_K_DEC_QKV_FINISH = 7, /* decode RoPE + cache append                          */
+  HYP_K_ATTN_DECODE = 8,    /* decode attention over the cache + chunk merge       */
+  HYP_K_GEMV_O = 9,
+  HYP_K_GEMV_GATEUP = 10,
+  HYP_K_DEC_SWIGLU = 11,
+  HYP_K_GEMV_DOWN = 12,
+  HYP_K_COUNT = 13
+} hyp_kernel_class_t;
+
+/* Measurement aid: from now on bracket every launch of the kernel classes in
+ * class_mask (bit i = class i) with a pair of HIP events on the stage's stream;
+ * 0 switches it off.  Either way the stream is synchronised and earlier records
+ * are dropped.  Host state only (events); no device memory is allocated. */
+HYP_API hyp_status_t stage_profile(hyp_stage_t *stage, uint32_t class_mask);
+
+/* Synchronise the stream and return the summed duration (milliseconds) and the
+ * number of launches of one kernel class recorded since stage_profile(). */
+HYP_API hyp_status_t stage_profile_read(hyp_stage_t *stage, int32_t kernel_class, double *total_ms,
+                                int64_t *launches);
+
 /* 1 if the MFMA kernels run for this stage, 0 if the shape-generic kernels do
  * (fp32 stages, head_dim != 128, widths that are not multiples of 256, or
  * HYP_FLAG_PLAIN_KERNELS). */

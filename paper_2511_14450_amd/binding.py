@@ -21,7 +21,10 @@ HYP_FLAG_PLAIN_KERNELS = 1
 
 EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_decode_step",
            "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",
-           "stage_uses_mfma")
+           "stage_uses_mfma", "stage_profile", "stage_profile_read")
+
+KERNEL_CLASSES = ("add_norm", "gemm_qkv", "attn_prefill", "gemm_o", "gemm_gateup", "gemm_down", "gemv_qkv",
+                  "dec_qkv_finish", "attn_decode", "gemv_o", "gemv_gateup", "dec_swiglu", "gemv_down")
 
 
 class HypError(RuntimeError):
@@ -43,6 +46,16 @@ _WEIGHT_FIELDS = ("attn_norm_g", "wq", "wk", "wv", "wo", "ffn_norm_g", "w_gate",
 
 class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
+
+
+def stage_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, flags: int = 0) -> StageConfig:
+    """StageConfig from any object with the block-shape attributes (hidden, n_q_heads,
+    n_kv_heads, head_dim, ffn_dim, rms_eps, rope_base, dtype in {"f32", "bf16"})."""
+    return StageConfig(hidden=shape.hidden, n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads,
+                       head_dim=shape.head_dim, ffn_dim=shape.ffn_dim, rms_eps=shape.rms_eps,
+                       rope_base=shape.rope_base, dtype=HYP_BF16 if shape.dtype == "bf16" else HYP_F32,
+                       max_batch=max_batch, max_seq=max_seq, max_prefill_tokens=max_prefill_tokens,
+                       flags=flags, reserved=0)
 
 
 def library_path() -> pathlib.Path:
@@ -76,6 +89,10 @@ def load_library() -> C.CDLL:
     lib.stage_destroy.argtypes = [C.c_void_p]
     lib.stage_last_error.restype = C.c_char_p
     lib.stage_last_error.argtypes = [C.c_void_p]
+    lib.stage_profile.restype = C.c_int
+    lib.stage_profile.argtypes = [C.c_void_p, C.c_uint32]
+    lib.stage_profile_read.restype = C.c_int
+    lib.stage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.stage_uses_mfma.restype = C.c_int32
     lib.stage_uses_mfma.argtypes = [C.c_void_p]
     _LIB = lib
@@ -118,6 +135,12 @@ class Stage:
 
     def context_len(self, request):
         return stage_context_len(self, request)
+
+    def profile(self, classes):
+        return stage_profile(self, classes)
+
+    def profile_read(self, kernel_class):
+        return stage_profile_read(self, kernel_class)
 
     def uses_mfma(self):
         return stage_uses_mfma(self)
@@ -212,6 +235,22 @@ def stage_export_kv(stage: Stage, layer: int, request: int):
     status = load_library().stage_export_kv(stage.handle, layer, request, k.data_ptr(), v.data_ptr())
     _check(status, stage.handle)
     return k, v
+
+
+def stage_profile(stage: Stage, classes: Sequence[str]) -> None:
+    """Start timing the named kernel classes (empty sequence: stop)."""
+    mask = 0
+    for c in classes:
+        mask |= 1 << KERNEL_CLASSES.index(c)
+    _check(load_library().stage_profile(stage.handle, mask), stage.handle)
+
+
+def stage_profile_read(stage: Stage, kernel_class: str):
+    """(total milliseconds, launches) of one kernel class since stage_profile()."""
+    ms, n = C.c_double(), C.c_int64()
+    _check(load_library().stage_profile_read(stage.handle, KERNEL_CLASSES.index(kernel_class), C.byref(ms), C.byref(n)),
+           stage.handle)
+    return ms.value, n.value
 
 
 def stage_uses_mfma(stage: Stage) -> bool:

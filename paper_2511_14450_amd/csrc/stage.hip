@@ -178,6 +178,11 @@ struct hyp_stage {
   hipEvent_t upload_done;
   bool upload_pending;
   std::vector<int> lens;  // host mirror of the cached lengths
+  // optional per-kernel-class timing with HIP events on the stage's stream
+  struct ProfSlot { hipEvent_t a, b; int cls; };
+  std::vector<ProfSlot> prof;
+  size_t prof_used = 0;
+  uint32_t prof_mask = 0;
   int batch;
   bool prefilled;
   std::string err;
@@ -195,6 +200,34 @@ hyp_status_t fail(hyp_stage *st, hyp_status_t code, const std::string &msg) {
     hipError_t e_ = (expr);                                                                      \
     if (e_ != hipSuccess)                                                                        \
       return fail(st, HYP_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_));           \
+  } while (0)
+
+// Launch `expr`; when kernel class `cls` is being profiled, bracket it with a
+// pair of events recorded on the stage's stream.
+hipError_t prof_begin(hyp_stage *st, int cls, int *slot) {
+  *slot = -1;
+  if (!(st->prof_mask & (1u << cls))) return hipSuccess;
+  if (st->prof_used == st->prof.size()) {
+    hyp_stage::ProfSlot ps;
+    hipError_t e = hipEventCreate(&ps.a);
+    if (e != hipSuccess) return e;
+    e = hipEventCreate(&ps.b);
+    if (e != hipSuccess) { (void)hipEventDestroy(ps.a); return e; }
+    st->prof.push_back(ps);
+  }
+  *slot = (int)st->prof_used++;
+  st->prof[*slot].cls = cls;
+  return hipEventRecord(st->prof[*slot].a, st->stream);
+}
+hipError_t prof_end(hyp_stage *st, int slot) {
+  return slot < 0 ? hipSuccess : hipEventRecord(st->prof[slot].b, st->stream);
+}
+#define PROF(st, cls, expr)                         \
+  do {                                              \
+    int slot_;                                      \
+    HIP_TRY(st, prof_begin(st, cls, &slot_));       \
+    HIP_TRY(st, expr);                              \
+    HIP_TRY(st, prof_end(st, slot_));               \
   } while (0)
 
 template <typename T> T *at(hyp_stage *st, size_t off) { return reinterpret_cast<T *>(st->ws + off); }
@@ -274,7 +307,7 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
   bf16_t *m = at<bf16_t>(st, L.m), *delta = at<bf16_t>(st, L.delta);
   const int *row_ext = at<int>(st, L.row_ext);
   CacheGeom geom = cache_geom(st);
-  HIP_TRY(st, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
+  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
                             nullptr, row_ext, rows, d.H, d.eps, false, s));
   for (int l = 0; l < st->n_layers; ++l) {
     const LayerPtrs &p = L.layers[l];
@@ -284,19 +317,19 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
     e.geom = geom; e.qd = d.qd; e.kvd = d.kvd;
     e.cos_tab = at<float>(st, L.cos_tab); e.sin_tab = at<float>(st, L.sin_tab);
     e.row_pos = at<int>(st, L.row_pos); e.row_req = at<int>(st, L.row_req);
-    HIP_TRY(st, mfma_gemm(EPI_QKV, y, at<bf16_t>(st, p.wqkv), rows, d.qd + 2 * d.kvd, d.H, q, d.qd, &e, s));
-    HIP_TRY(st, mfma_attn_prefill(q, e.Kc, e.Vc, geom, attn, at<PrefillTile>(st, L.tiles), n_tiles,
+    PROF(st, HYP_K_GEMM_QKV, mfma_gemm(EPI_QKV, y, at<bf16_t>(st, p.wqkv), rows, d.qd + 2 * d.kvd, d.H, q, d.qd, &e, s));
+    PROF(st, HYP_K_ATTN_PREFILL, mfma_attn_prefill(q, e.Kc, e.Vc, geom, attn, at<PrefillTile>(st, L.tiles), n_tiles,
                                   at<int>(st, L.req_len), d.nq, d.nkv, s));
-    HIP_TRY(st, mfma_gemm(EPI_STORE, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, delta, d.H, nullptr, s));
-    HIP_TRY(st, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, p.g2), y, nullptr, row_ext, rows, d.H,
+    PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_STORE, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, delta, d.H, nullptr, s));
+    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, p.g2), y, nullptr, row_ext, rows, d.H,
                               d.eps, false, s));
-    HIP_TRY(st, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, nullptr, s));
-    HIP_TRY(st, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, nullptr, s));
+    PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, nullptr, s));
+    PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, nullptr, s));
     if (l + 1 < st->n_layers)
-      HIP_TRY(st, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, L.layers[l + 1].g1), y, nullptr,
+      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, L.layers[l + 1].g1), y, nullptr,
                                 row_ext, rows, d.H, d.eps, false, s));
     else
-      HIP_TRY(st, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, nullptr, nullptr, (bf16_t *)hidden_out, row_ext, rows,
+      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, nullptr, nullptr, (bf16_t *)hidden_out, row_ext, rows,
                                 d.H, d.eps, true, s));
   }
   return HYP_OK;
@@ -315,26 +348,26 @@ hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_
   const float *ct = at<float>(st, L.cos_tab), *sn = at<float>(st, L.sin_tab);
   CacheGeom geom = cache_geom(st);
   const int Nqkv = d.qd + 2 * d.kvd;
-  HIP_TRY(st, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
+  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
                             nullptr, row_ext, 32, d.H, d.eps, false, s));
   for (int l = 0; l < st->n_layers; ++l) {
     const LayerPtrs &p = L.layers[l];
     bf16_t *Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l), *Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
-    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wqkv), y, part, Nqkv, d.H, L.ks_qkv, B, s));
-    HIP_TRY(st, mfma_dec_qkv_finish(part, L.ks_qkv, Nqkv, lens, ct, sn, qdec, Kc, Vc, geom, d.nq, d.nkv, B, s));
-    HIP_TRY(st, mfma_attn_decode(qdec, Kc, Vc, geom, lens, at<float>(st, L.attn_part), attn, d.nq, d.nkv, B,
+    PROF(st, HYP_K_GEMV_QKV, mfma_gemv(at<bf16_t>(st, p.wqkv), y, part, Nqkv, d.H, L.ks_qkv, B, s));
+    PROF(st, HYP_K_DEC_QKV_FINISH, mfma_dec_qkv_finish(part, L.ks_qkv, Nqkv, lens, ct, sn, qdec, Kc, Vc, geom, d.nq, d.nkv, B, s));
+    PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(qdec, Kc, Vc, geom, lens, at<float>(st, L.attn_part), attn, d.nq, d.nkv, B,
                                  L.max_chunks, s));
-    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wo), attn, part, d.H, d.qd, L.ks_o, B, s));
-    HIP_TRY(st, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_o, (size_t)d.H * 32, at<bf16_t>(st, p.g2), y, nullptr,
+    PROF(st, HYP_K_GEMV_O, mfma_gemv(at<bf16_t>(st, p.wo), attn, part, d.H, d.qd, L.ks_o, B, s));
+    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_o, (size_t)d.H * 32, at<bf16_t>(st, p.g2), y, nullptr,
                               row_ext, 32, d.H, d.eps, false, s));
-    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wgu), y, part, 2 * d.I, d.H, L.ks_gu, B, s));
-    HIP_TRY(st, mfma_dec_swiglu(part, L.ks_gu, d.I, m, B, s));
-    HIP_TRY(st, mfma_gemv(at<bf16_t>(st, p.wd), m, part, d.H, d.I, L.ks_d, B, s));
+    PROF(st, HYP_K_GEMV_GATEUP, mfma_gemv(at<bf16_t>(st, p.wgu), y, part, 2 * d.I, d.H, L.ks_gu, B, s));
+    PROF(st, HYP_K_DEC_SWIGLU, mfma_dec_swiglu(part, L.ks_gu, d.I, m, B, s));
+    PROF(st, HYP_K_GEMV_DOWN, mfma_gemv(at<bf16_t>(st, p.wd), m, part, d.H, d.I, L.ks_d, B, s));
     if (l + 1 < st->n_layers)
-      HIP_TRY(st, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, at<bf16_t>(st, L.layers[l + 1].g1),
+      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, at<bf16_t>(st, L.layers[l + 1].g1),
                                 y, nullptr, row_ext, 32, d.H, d.eps, false, s));
     else
-      HIP_TRY(st, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, nullptr, nullptr,
+      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, nullptr, nullptr,
                                 (bf16_t *)hidden_out, row_ext, 32, d.H, d.eps, true, s));
   }
   return HYP_OK;
@@ -592,10 +625,37 @@ hyp_status_t stage_context_len(const hyp_stage_t *st, int32_t request, int32_t *
   return HYP_OK;
 }
 
+hyp_status_t stage_profile(hyp_stage_t *st, uint32_t class_mask) {
+  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+  HIP_TRY(st, hipStreamSynchronize(st->stream));
+  st->prof_mask = class_mask;
+  st->prof_used = 0;
+  return HYP_OK;
+}
+
+hyp_status_t stage_profile_read(hyp_stage_t *st, int32_t kernel_class, double *total_ms, int64_t *launches) {
+  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+  if (!total_ms || !launches || kernel_class < 0 || kernel_class >= HYP_K_COUNT) return fail(st, HYP_EINVAL, "bad argument");
+  HIP_TRY(st, hipStreamSynchronize(st->stream));
+  double tot = 0;
+  int64_t n = 0;
+  for (size_t i = 0; i < st->prof_used; ++i) {
+    if (st->prof[i].cls != kernel_class) continue;
+    float ms = 0.f;
+    HIP_TRY(st, hipEventElapsedTime(&ms, st->prof[i].a, st->prof[i].b));
+    tot += ms;
+    ++n;
+  }
+  *total_ms = tot;
+  *launches = n;
+  return HYP_OK;
+}
+
 hyp_status_t stage_destroy(hyp_stage_t *st) {
   if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
   if (st->upload_done) (void)hipEventDestroy(st->upload_done);
   if (st->h_stage) (void)hipHostFree(st->h_stage);
+  for (auto &ps : st->prof) { (void)hipEventDestroy(ps.a); (void)hipEventDestroy(ps.b); }
   delete st;
   return HYP_OK;
 }

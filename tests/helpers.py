@@ -30,12 +30,7 @@ def to_host(t) -> np.ndarray:
 
 def make_config(shape: synth.BlockShape, max_batch: int, max_seq: int, max_prefill: int, flags: int = 0):
     import paper_2511_14450_amd as hyp
-    from paper_2511_14450_amd import binding
-    return hyp.StageConfig(
-        hidden=shape.hidden, n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads,
-        head_dim=shape.head_dim, ffn_dim=shape.ffn_dim, rms_eps=shape.rms_eps,
-        rope_base=shape.rope_base, dtype=binding.HYP_BF16 if shape.dtype == "bf16" else binding.HYP_F32,
-        max_batch=max_batch, max_seq=max_seq, max_prefill_tokens=max_prefill, flags=flags, reserved=0)
+    return hyp.stage_config(shape, max_batch, max_seq, max_prefill, flags)
 
 
 def make_gpu_stage(shape, layers_np, max_batch, max_seq, max_prefill, l_start=0, flags=0):

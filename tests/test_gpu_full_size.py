@@ -1,0 +1,81 @@
+"""Parity at the full Phi-3-medium block shape, in the launch configuration the
+bench times (MFMA path, real widths, long and ragged contexts).  The oracle
+cannot run 100+ TFLOP stages, so a one-block stage is checked on sampled rows:
+the oracle forms keys and values for every position of a sampled request and
+the complete block output for the sampled query rows (first, last, tile edges,
+random), then follows with cached decode steps at the full context length."""
+import numpy as np
+import pytest
+
+from oracle import hyp_oracle as orc
+from workloads import synth
+from tests.helpers import make_gpu_stage, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+SHAPE = synth.PHI3_MEDIUM
+
+
+@pytest.fixture(scope="module")
+def phi3_layer():
+    return synth.layer_weights(SHAPE, 0, synth.WORKLOADS["c3_stage10"].seed)
+
+
+def sample_rows(L, rng, n_random=6):
+    edges = [0, 1, 31, 32, 63, 64, 65, 127, 128, 255, 256, 257, L - 2, L - 1]
+    rows = sorted({r for r in edges if 0 <= r < L} | {int(v) for v in rng.integers(0, L, n_random)})
+    return rows
+
+
+def check_requests(layer, lens, seed, sample_reqs, decode_steps):
+    B, T = len(lens), sum(lens)
+    cap = max(lens) + decode_steps
+    x = synth.hidden_states(T, SHAPE, seed)
+    gst = make_gpu_stage(SHAPE, [layer], B, cap, T)
+    assert gst.uses_mfma()
+    got = to_host(gst.prefill(to_dev(x, "bf16"), lens))
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    rng = np.random.default_rng(seed)
+    caches = {}
+    worst = 0.0
+    for b in sample_reqs:
+        L = lens[b]
+        xb = x[starts[b]: starts[b] + L]
+        rows = sample_rows(L, rng)
+        Kc, Vc = orc.new_cache(SHAPE, L + decode_steps)
+        ref = orc.layer_forward(SHAPE, layer, xb, 0, Kc, Vc, rows=rows)
+        g = got[starts[b]: starts[b] + L][rows]
+        e = rel_err(g, ref)
+        eu = rel_err(g - xb[rows], ref - xb[rows])
+        assert e <= TOL and eu <= TOL + 2.0 ** -8 * np.abs(ref).max() / np.abs(ref - xb[rows]).max(), (b, e, eu)
+        worst = max(worst, e)
+        # the cache the GPU built for this request, against the oracle's
+        k, v = gst.export_kv(0, b)
+        assert rel_err(to_host(k), Kc[:L]) <= TOL and rel_err(to_host(v), Vc[:L]) <= TOL
+        caches[b] = (Kc, Vc)
+    for s in range(decode_steps):
+        xd = synth.hidden_states(B, SHAPE, seed + 100 + s)
+        gd = to_host(gst.decode_step(to_dev(xd, "bf16")))
+        for b in sample_reqs:
+            Kc, Vc = caches[b]
+            ref = orc.layer_forward(SHAPE, layer, xd[b: b + 1], lens[b] + s, Kc, Vc)
+            e = rel_err(gd[b], ref[0])
+            assert e <= TOL, (s, b, e)
+            worst = max(worst, e)
+    gst.destroy()
+    return worst
+
+
+def test_c2_layer_4x512_sampled_rows(phi3_layer):
+    check_requests(phi3_layer, [512] * 4, 9100, sample_reqs=[0, 3], decode_steps=0)
+
+
+def test_c3_layer_8x2048_sampled_rows_then_decode(phi3_layer):
+    check_requests(phi3_layer, [2048] * 8, 9200, sample_reqs=[0, 5], decode_steps=2)
+
+
+def test_c4_ragged_batch32_decode_at_long_context(phi3_layer):
+    lens = synth.WORKLOADS["c4_decode_heavy"].lengths()
+    assert len(lens) == 32 and min(lens) >= 1024 and max(lens) <= 4096
+    longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
+    check_requests(phi3_layer, lens, 9300, sample_reqs=[longest, shortest], decode_steps=2)

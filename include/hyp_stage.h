@@ -60,6 +60,8 @@ typedef enum {
 typedef enum { HYP_F32 = 0, HYP_BF16 = 1 } hyp_dtype_t;
 
 /* hyp_stage_config_t.flags */
+#define HYP_FLAG_NO_GRAPH 2u      /* launch the decode-step kernels one by one instead of replaying \
+                                     a recorded HIP graph                                 */
 #define HYP_FLAG_PLAIN_KERNELS 1u /* diagnostics: run the shape-generic HIP kernels even \
                                      where the MFMA kernels apply                        */
 

@@ -18,6 +18,7 @@ HYP_OK, HYP_EINVAL, HYP_ESHAPE, HYP_ECAPACITY, HYP_ESTATE, HYP_EDEVICE, HYP_ENOM
 STATUS_NAMES = ["HYP_OK", "HYP_EINVAL", "HYP_ESHAPE", "HYP_ECAPACITY", "HYP_ESTATE", "HYP_EDEVICE", "HYP_ENOMEM"]
 HYP_F32, HYP_BF16 = 0, 1
 HYP_FLAG_PLAIN_KERNELS = 1
+HYP_FLAG_NO_GRAPH = 2
 
 EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_decode_step",
            "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",

@@ -201,14 +201,16 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  for (int kb = kb_begin; kb < kb_end; ++kb) {
+  bf16x8_t kA[8], vA[8], kB[8], vB[8];
+  auto load_block = [&](int kb, bf16x8_t *kf, bf16x8_t *vf) {
     const bf16_t *kblk = Kc + geom.off(req, kvh, kb) + lane * 8;
     const bf16_t *vblk = Vc + geom.off(req, kvh, kb) + lane * 8;
-    bf16x8_t kf[8], vf[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) kf[t] = *(const bf16x8_t *)(kblk + t * kTileElems);
+    for (int t = 0; t < 8; ++t) kf[t] = __builtin_nontemporal_load((const bf16x8_t *)(kblk + t * kTileElems));
 #pragma unroll
-    for (int t = 0; t < 8; ++t) vf[t] = *(const bf16x8_t *)(vblk + t * kTileElems);
+    for (int t = 0; t < 8; ++t) vf[t] = __builtin_nontemporal_load((const bf16x8_t *)(vblk + t * kTileElems));
+  };
+  auto compute_block = [&](int kb, const bf16x8_t *kf, const bf16x8_t *vf) {
     f32x16_t s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -243,6 +245,16 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
     for (int db = 0; db < 4; ++db) {
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db], pf0, o[db], 0, 0, 0);
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[4 + db], pf1, o[db], 0, 0, 0);
+    }
+  };
+  // two register sets: the loads of the next block are in flight while this one is used
+  load_block(kb_begin, kA, vA);
+  for (int kb = kb_begin; kb < kb_end; kb += 2) {
+    if (kb + 1 < kb_end) load_block(kb + 1, kB, vB);
+    compute_block(kb, kA, vA);
+    if (kb + 1 < kb_end) {
+      if (kb + 2 < kb_end) load_block(kb + 2, kA, vA);
+      compute_block(kb + 1, kB, vB);
     }
   }
   // lanes tl < G hold real heads

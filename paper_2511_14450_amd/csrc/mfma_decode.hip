@@ -10,7 +10,7 @@ namespace hyp {
 namespace {
 
 // ----------------------------------------------------------------------------
-// partial[ks][n][32] = sum over the K slice ks of W[n, k] x[token, k]
+// partial[ks][token][n] = sum over the K slice ks of W[n, k] x[token, k]
 // W = P(N, K): the 1 KiB tiles of one 32-row block are contiguous along K, and a
 // tile is the MFMA A fragment as it stands, so every wave streams its slice
 // with 1 KiB fully coalesced loads straight into registers (no LDS on the way
@@ -65,16 +65,17 @@ __global__ void __launch_bounds__(NW * 64) k_gemv(const bf16_t *__restrict__ W,
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[wave][i][r][lane] = acc[i][r];
   __syncthreads();
-  // thread -> (block i, register r, lane l): feature = 8g + 4hh + e, token = l % 32
-  for (int idx = threadIdx.x; idx < FBW * 16 * 64; idx += NW * 64) {
-    int l = idx & 63, r = (idx >> 6) & 15, i = idx >> 10;
-    int token = l & 31;
-    if (token >= batch) continue;
+  // thread -> (token, feature f of the FBW*32 this workgroup owns): consecutive threads
+  // write consecutive features of one token row
+  for (int idx = threadIdx.x; idx < FBW * 32 * 32; idx += NW * 64) {
+    int f = idx % (FBW * 32), token = idx / (FBW * 32);
+    if (token >= batch) break;
+    int i = f >> 5, fl = f & 31;
+    int r = ((fl >> 3) << 2) + (fl & 3), l = (((fl >> 2) & 1) << 5) + token;
     float sum = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) sum += red[w][i][r][l];
-    int n = (fb0 + i) * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-    partial[((size_t)ks * N + n) * 32 + token] = sum;
+    partial[((size_t)ks * 32 + token) * N + fb0 * 32 + f] = sum;
   }
 }
 
@@ -95,8 +96,8 @@ __global__ void __launch_bounds__(64) k_dec_qkv_finish(const float *__restrict__
   float a = 0.f, c = 0.f;
   int r0 = packed_row_qkv(head, i), r1 = packed_row_qkv(head, i + 64);
   for (int s = 0; s < ksplit; ++s) {
-    a += partial[((size_t)s * N + r0) * 32 + b];
-    c += partial[((size_t)s * N + r1) * 32 + b];
+    a += partial[((size_t)s * 32 + b) * N + r0];
+    c += partial[((size_t)s * 32 + b) * N + r1];
   }
   if (head < nq + nkv) {
     float cs = cos_tab[(size_t)pos * 64 + i], sn = sin_tab[(size_t)pos * 64 + i];
@@ -128,8 +129,8 @@ __global__ void __launch_bounds__(256) k_dec_swiglu(const float *__restrict__ pa
   int rg = (f >> 7) * 256 + ((f & 127) >> 5) * 64 + (f & 31), ru = rg + 32;
   float g = 0.f, u = 0.f;
   for (int s = 0; s < ksplit; ++s) {
-    g += partial[((size_t)s * N + rg) * 32 + b];
-    u += partial[((size_t)s * N + ru) * 32 + b];
+    g += partial[((size_t)s * 32 + b) * N + rg];
+    u += partial[((size_t)s * 32 + b) * N + ru];
   }
   m[frag_offset(b, f, I)] = f2bf_dev(g / (1.0f + __expf(-g)) * u);
 }

@@ -41,7 +41,7 @@ hipError_t mfma_attn_prefill(const bf16_t *q, const bf16_t *Kc, const bf16_t *Vc
                              int nq, int nkv, hipStream_t s);
 
 // ------------------------------------------------------------------ decode
-// partial[ks][N][32] (fp32, token fastest) = W[N, K-slice ks] x[32 rows, K-slice]^T, tokens < batch only
+// partial[ks][32][N] (fp32) = x[32 rows, K-slice ks] W[N, K-slice]^T, token rows < batch only
 hipError_t mfma_gemv(const bf16_t *W, const bf16_t *x, float *partial, int N, int K, int ksplit,
                      int batch, hipStream_t s);
 int mfma_gemv_ksplit(int N, int K);
@@ -56,7 +56,7 @@ hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *
                             const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
                             int max_chunks, hipStream_t s);
 size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks);
-constexpr int kDecodeChunkKeys = 256;
+constexpr int kDecodeChunkKeys = 128;
 // m = silu(gate) * up from the gate/up partials -> P(32, I)
 hipError_t mfma_dec_swiglu(const float *partial, int ksplit, int I, bf16_t *m, int batch, hipStream_t s);
 

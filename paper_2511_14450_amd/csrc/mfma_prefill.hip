@@ -53,11 +53,12 @@ __global__ void __launch_bounds__(256) k_pack_weight(const bf16_t *__restrict__ 
 //   xres = x;  y = x * rsqrt(mean(x^2) + eps) * g   -> P(rows, H)   (norm mode)
 //   hidden_out[row_ext] = x                                           (final mode)
 // delta is either one fragment-order bf16 matrix P(rows, H) (prefill GEMM
-// output) or n_part fp32 partial sums [n_part][H][32] (decode split-K output,
-// rows = tokens < 32).
-// A 256-thread block owns 8 consecutive rows; thread t works on row t % 8.
+// output) or n_part fp32 partial sums [n_part][32][H] (decode split-K output).
+// A 256-thread block owns RPW consecutive rows (8 for prefill, 1 for the few rows
+// of a decode step so that more workgroups share the latency-bound sums);
+// thread t works on row t % RPW.
 // ----------------------------------------------------------------------------
-template <int MODE>  // 0: norm -> y ; 1: final -> hidden_out
+template <int MODE, int RPW>  // MODE 0: norm -> y ; 1: final -> hidden_out
 __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hidden_in,
                                                   float *__restrict__ xres,
                                                   const bf16_t *__restrict__ delta_bf,
@@ -65,14 +66,15 @@ __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hid
                                                   size_t part_stride, const bf16_t *__restrict__ gain,
                                                   bf16_t *__restrict__ y, bf16_t *__restrict__ hidden_out,
                                                   const int *__restrict__ row_ext, int H, float eps) {
-  __shared__ float red[8][33];
-  int r8 = threadIdx.x & 7, cg = threadIdx.x >> 3;  // cg: 0..31 chunk lane
-  int row = blockIdx.x * 8 + r8;
+  constexpr int CPR = 256 / RPW;  // threads per row
+  __shared__ float red[RPW][CPR + 1];
+  int r8 = threadIdx.x % RPW, cg = threadIdx.x / RPW;
+  int row = blockIdx.x * RPW + r8;
   int ext = row_ext[row];
   int nchunk = H >> 3;
   float ss = 0.f;
   float *xr = xres + (size_t)row * H;
-  for (int c = cg; c < nchunk; c += 32) {
+  for (int c = cg; c < nchunk; c += CPR) {
     float v[8];
     if (ext < 0) {
       for (int e = 0; e < 8; ++e) v[e] = 0.f;
@@ -89,8 +91,9 @@ __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hid
         for (int e = 0; e < 8; ++e) v[e] += bf16_to_f32(d.v[e]);
       }
       for (int s = 0; s < n_part; ++s) {
-        const float *p = delta_part + s * part_stride + (size_t)(c * 8) * 32 + row;  // [n][32 tokens]
-        for (int e = 0; e < 8; ++e) v[e] += p[e * 32];
+        const float *p = delta_part + s * part_stride + (size_t)row * H + c * 8;
+        f32x4_t a = *(const f32x4_t *)p, b = *(const f32x4_t *)(p + 4);
+        for (int e = 0; e < 4; ++e) { v[e] += a[e]; v[4 + e] += b[e]; }
       }
     }
     if (MODE == 0) {
@@ -109,9 +112,9 @@ __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hid
   red[r8][cg] = ss;
   __syncthreads();
   float tot = 0.f;
-  for (int i = 0; i < 32; ++i) tot += red[r8][i];
+  for (int i = 0; i < CPR; ++i) tot += red[r8][i];
   float rs = 1.0f / sqrtf(tot / (float)H + eps);
-  for (int c = cg; c < nchunk; c += 32) {
+  for (int c = cg; c < nchunk; c += CPR) {
     f32x4_t a = *(const f32x4_t *)(xr + c * 8), b = *(const f32x4_t *)(xr + c * 8 + 4);
     u16x8_t gg = *(const u16x8_t *)(gain + c * 8);
     u16x8_t o;
@@ -386,10 +389,14 @@ hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *del
                          bf16_t *y, bf16_t *hidden_out, const int *row_ext, int rows, int H, float eps,
                          bool final_mode, hipStream_t s) {
   if (rows == 0) return hipSuccess;
-  if (final_mode)
-    k_add_norm<1><<<rows / 8, 256, 0, s>>>(hidden_in, xres, delta_bf, delta_part, n_part, part_stride, gain, y, hidden_out, row_ext, H, eps);
-  else
-    k_add_norm<0><<<rows / 8, 256, 0, s>>>(hidden_in, xres, delta_bf, delta_part, n_part, part_stride, gain, y, hidden_out, row_ext, H, eps);
+#define HYP_ADD_NORM(MODE, RPW) \
+  k_add_norm<MODE, RPW><<<rows / RPW, 256, 0, s>>>(hidden_in, xres, delta_bf, delta_part, n_part, part_stride, gain, y, hidden_out, row_ext, H, eps)
+  if (rows <= 64) {
+    if (final_mode) HYP_ADD_NORM(1, 1); else HYP_ADD_NORM(0, 1);
+  } else {
+    if (final_mode) HYP_ADD_NORM(1, 8); else HYP_ADD_NORM(0, 8);
+  }
+#undef HYP_ADD_NORM
   return hipGetLastError();
 }
 

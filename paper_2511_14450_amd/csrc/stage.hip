@@ -183,6 +183,11 @@ struct hyp_stage {
   std::vector<ProfSlot> prof;
   size_t prof_used = 0;
   uint32_t prof_mask = 0;
+  // the layer loop of a decode step, captured once per batch size and replayed
+  hipGraph_t dec_graph = nullptr;
+  hipGraphExec_t dec_exec = nullptr;
+  int dec_graph_batch = 0;
+  hipStream_t cap_stream = nullptr;  // recording only (the null stream cannot be captured); nothing runs on it
   int batch;
   bool prefilled;
   std::string err;
@@ -335,10 +340,11 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
   return HYP_OK;
 }
 
-// one decode step through the MFMA kernels: a single block of 32 token rows
-hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_out) {
+// the part of a decode step that touches only the stage's own buffers: every
+// kernel between the first residual/norm (reads hidden_in) and the last one
+// (writes hidden_out)
+hyp_status_t decode_layers_mfma(hyp_stage *st, hipStream_t s) {
   const Dims &d = st->dm;
-  hipStream_t s = st->stream;
   const Layout &L = st->L;
   const int B = st->batch;
   float *xres = at<float>(st, L.xres), *part = at<float>(st, L.partial);
@@ -348,8 +354,6 @@ hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_
   const float *ct = at<float>(st, L.cos_tab), *sn = at<float>(st, L.sin_tab);
   CacheGeom geom = cache_geom(st);
   const int Nqkv = d.qd + 2 * d.kvd;
-  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
-                            nullptr, row_ext, 32, d.H, d.eps, false, s));
   for (int l = 0; l < st->n_layers; ++l) {
     const LayerPtrs &p = L.layers[l];
     bf16_t *Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l), *Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
@@ -358,18 +362,62 @@ hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_
     PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(qdec, Kc, Vc, geom, lens, at<float>(st, L.attn_part), attn, d.nq, d.nkv, B,
                                  L.max_chunks, s));
     PROF(st, HYP_K_GEMV_O, mfma_gemv(at<bf16_t>(st, p.wo), attn, part, d.H, d.qd, L.ks_o, B, s));
-    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_o, (size_t)d.H * 32, at<bf16_t>(st, p.g2), y, nullptr,
+    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_o, (size_t)32 * d.H, at<bf16_t>(st, p.g2), y, nullptr,
                               row_ext, 32, d.H, d.eps, false, s));
     PROF(st, HYP_K_GEMV_GATEUP, mfma_gemv(at<bf16_t>(st, p.wgu), y, part, 2 * d.I, d.H, L.ks_gu, B, s));
     PROF(st, HYP_K_DEC_SWIGLU, mfma_dec_swiglu(part, L.ks_gu, d.I, m, B, s));
     PROF(st, HYP_K_GEMV_DOWN, mfma_gemv(at<bf16_t>(st, p.wd), m, part, d.H, d.I, L.ks_d, B, s));
     if (l + 1 < st->n_layers)
-      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, at<bf16_t>(st, L.layers[l + 1].g1),
+      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)32 * d.H, at<bf16_t>(st, L.layers[l + 1].g1),
                                 y, nullptr, row_ext, 32, d.H, d.eps, false, s));
-    else
-      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)d.H * 32, nullptr, nullptr,
-                                (bf16_t *)hidden_out, row_ext, 32, d.H, d.eps, true, s));
   }
+  return HYP_OK;
+}
+
+void drop_decode_graph(hyp_stage *st) {
+  if (st->dec_exec) (void)hipGraphExecDestroy(st->dec_exec);
+  if (st->dec_graph) (void)hipGraphDestroy(st->dec_graph);
+  st->dec_exec = nullptr;
+  st->dec_graph = nullptr;
+}
+
+// one decode step through the MFMA kernels: a single block of 32 token rows.
+// The ~10 launches per block are latency-bound next to ~0.1 ms of streaming, so
+// the layer loop is recorded into a HIP graph (kernel nodes only) the first time
+// a batch size is seen and replayed afterwards; while kernel classes are being
+// timed, or when the caller is itself capturing the stream, it is launched
+// kernel by kernel instead.
+hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_out) {
+  const Dims &d = st->dm;
+  hipStream_t s = st->stream;
+  const Layout &L = st->L;
+  float *xres = at<float>(st, L.xres), *part = at<float>(st, L.partial);
+  const int *row_ext = at<int>(st, L.row_ext_dec);
+  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1),
+                            at<bf16_t>(st, L.y), nullptr, row_ext, 32, d.H, d.eps, false, s));
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  HIP_TRY(st, hipStreamIsCapturing(s, &cap));
+  bool use_graph = st->prof_mask == 0 && cap == hipStreamCaptureStatusNone && !(st->cfg.flags & HYP_FLAG_NO_GRAPH);
+  if (use_graph) {
+    if (!st->dec_exec || st->dec_graph_batch != st->batch) {
+      drop_decode_graph(st);
+      if (!st->cap_stream) HIP_TRY(st, hipStreamCreateWithFlags(&st->cap_stream, hipStreamNonBlocking));
+      HIP_TRY(st, hipStreamBeginCapture(st->cap_stream, hipStreamCaptureModeThreadLocal));
+      hyp_status_t rc = decode_layers_mfma(st, st->cap_stream);
+      hipError_t e = hipStreamEndCapture(st->cap_stream, &st->dec_graph);
+      if (rc != HYP_OK) { drop_decode_graph(st); return rc; }
+      if (e != hipSuccess) { drop_decode_graph(st); return fail(st, HYP_EDEVICE, std::string("hipStreamEndCapture: ") + hipGetErrorString(e)); }
+      e = hipGraphInstantiate(&st->dec_exec, st->dec_graph, nullptr, nullptr, 0);
+      if (e != hipSuccess) { drop_decode_graph(st); return fail(st, HYP_EDEVICE, std::string("hipGraphInstantiate: ") + hipGetErrorString(e)); }
+      st->dec_graph_batch = st->batch;
+    }
+    HIP_TRY(st, hipGraphLaunch(st->dec_exec, s));
+  } else {
+    hyp_status_t rc = decode_layers_mfma(st, s);
+    if (rc != HYP_OK) return rc;
+  }
+  PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)32 * d.H, nullptr, nullptr,
+                            (bf16_t *)hidden_out, row_ext, 32, d.H, d.eps, true, s));
   return HYP_OK;
 }
 
@@ -656,6 +704,8 @@ hyp_status_t stage_destroy(hyp_stage_t *st) {
   if (st->upload_done) (void)hipEventDestroy(st->upload_done);
   if (st->h_stage) (void)hipHostFree(st->h_stage);
   for (auto &ps : st->prof) { (void)hipEventDestroy(ps.a); (void)hipEventDestroy(ps.b); }
+  drop_decode_graph(st);
+  if (st->cap_stream) (void)hipStreamDestroy(st->cap_stream);
   delete st;
   return HYP_OK;
 }

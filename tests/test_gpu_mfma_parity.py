@@ -103,3 +103,30 @@ def test_mfma_determinism_and_reprefill():
     d2 = st.decode_step(x1[:2].contiguous())
     assert torch.equal(y1, y2) and torch.equal(d1, d2)
     st.destroy()
+
+
+def test_decode_graph_replays_equal_kernel_by_kernel_launches():
+    """The recorded decode-step graph is replayed many times, with prefill calls and
+    synchronisations in between, and must give bit-identical results to launching
+    the same kernels one by one."""
+    import torch
+    from paper_2511_14450_amd import binding
+    shape = SHAPE_G2
+    layers = [synth.layer_weights(shape, l, 708, sigma=0.05) for l in range(2)]
+    lens = [40, 100, 7]
+    x = to_dev(synth.hidden_states(sum(lens), shape, 709), "bf16")
+    a = make_gpu_stage(shape, layers, 3, 200, 200)
+    b = make_gpu_stage(shape, layers, 3, 200, 200, flags=binding.HYP_FLAG_NO_GRAPH)
+    for rep in range(2):
+        ya, yb = a.prefill(x, lens), b.prefill(x, lens)
+        assert torch.equal(ya, yb)
+        for s in range(6):
+            xd = to_dev(synth.hidden_states(3, shape, 710 + s), "bf16")
+            da, db = a.decode_step(xd), b.decode_step(xd)
+            torch.cuda.synchronize()
+            assert torch.equal(da, db), (rep, s)
+        # a different batch size forces a new recording
+        a.prefill(x[:47].contiguous(), [40, 7]); b.prefill(x[:47].contiguous(), [40, 7])
+        xd = to_dev(synth.hidden_states(2, shape, 720), "bf16")
+        assert torch.equal(a.decode_step(xd), b.decode_step(xd))
+    a.destroy(); b.destroy()

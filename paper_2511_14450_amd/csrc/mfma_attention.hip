@@ -167,10 +167,10 @@ __global__ void __launch_bounds__(256) k_attn_prefill(const bf16_t *__restrict__
 // rows 0..G-1 of a P(32, 128) block (other rows zero), so the same MFMA shape
 // serves: S^T[key, head] = K q^T.  K and V fragments go straight from HBM into
 // registers (fragment order = operand order), 16 wave loads of 1 KiB per 32-key
-// block, no LDS.  One wave owns a chunk of kDecodeChunkKeys keys of one
+// block, no LDS.  One wave owns a chunk of chunk_keys keys of one
 // (request, KV head); chunks balance ragged contexts by tokens.  Every chunk
-// writes (max, sum, unnormalised output) and a second kernel merges the chunks
-// of a head in index order, so the result does not depend on scheduling.
+// writes (max, sum, unnormalised output) and a second small kernel merges the
+// chunks of a head in index order, so the result does not depend on scheduling.
 // part layout: [request][head][chunk][130] = {m, l, o[128]}
 // ----------------------------------------------------------------------------
 constexpr int kPartStride = 130;
@@ -179,14 +179,14 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
                                                     const bf16_t *__restrict__ Kc,
                                                     const bf16_t *__restrict__ Vc, CacheGeom geom,
                                                     const int *__restrict__ lens, float *__restrict__ part,
-                                                    int nq, int G, int max_chunks) {
+                                                    int nq, int G, int max_chunks, int chunk_keys) {
   const int lane = threadIdx.x, hh = lane >> 5, tl = lane & 31;
   const int chunk = blockIdx.x, kvh = blockIdx.y, req = blockIdx.z;
   const int nkeys = lens[req] + 1;  // the new token's key is already in the cache
-  const int k0 = chunk * kDecodeChunkKeys;
+  const int k0 = chunk * chunk_keys;
   if (k0 >= nkeys) return;
   const int kb_begin = k0 >> 5;
-  const int kb_end = min((k0 + kDecodeChunkKeys) >> 5, (nkeys + 31) >> 5);
+  const int kb_end = min((k0 + chunk_keys) >> 5, (nkeys + 31) >> 5);
   const float c = kLog2e * 0.08838834764831845f;
 
   bf16x8_t qf[8];
@@ -270,24 +270,42 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
   }
 }
 
-// one 128-thread block per (request, head): combine the chunks in order
+// One 128-thread block per (request, query head): combine its chunks in chunk
+// order.  Lane i of the first wave takes chunk i (max, sum -> weight); then thread
+// d accumulates output feature d over all chunks, eight loads in flight at a time.
 __global__ void __launch_bounds__(128) k_attn_decode_merge(const float *__restrict__ part,
                                                            const int *__restrict__ lens,
                                                            bf16_t *__restrict__ out, int nq,
-                                                           int max_chunks) {
+                                                           int max_chunks, int chunk_keys) {
+  __shared__ float wgt[64];
+  __shared__ float lsum;
   const int head = blockIdx.x, req = blockIdx.y, d = threadIdx.x;
-  const int n_chunks = (lens[req] + 1 + kDecodeChunkKeys - 1) / kDecodeChunkKeys;
-  const float *src = part + ((size_t)req * nq + head) * max_chunks * kPartStride;
+  const int n_chunks = (lens[req] + 1 + chunk_keys - 1) / chunk_keys;  // <= 64 by the host's choice of chunk_keys
   const float c = kLog2e * 0.08838834764831845f;
-  float m = -INFINITY;
-  for (int i = 0; i < n_chunks; ++i) m = fmaxf(m, src[i * kPartStride]);
-  float l = 0.f, acc = 0.f;
-  for (int i = 0; i < n_chunks; ++i) {
-    float w = exp2f((src[i * kPartStride] - m) * c);
-    l += w * src[i * kPartStride + 1];
-    acc += w * src[i * kPartStride + 2 + d];
+  const float *src = part + ((size_t)req * nq + head) * max_chunks * kPartStride;
+  if (d < 64) {
+    float mi = d < n_chunks ? src[d * kPartStride] : -INFINITY;
+    float li = d < n_chunks ? src[d * kPartStride + 1] : 0.f;
+    float m = mi;
+    for (int o2 = 32; o2 > 0; o2 >>= 1) m = fmaxf(m, __shfl_xor(m, o2, 64));
+    float w = d < n_chunks ? exp2f((mi - m) * c) : 0.f;
+    wgt[d] = w;
+    float wl = w * li, tot = 0.f;
+    for (int i = 0; i < n_chunks; ++i) tot += __shfl(wl, i, 64);  // chunk order
+    if (d == 0) lsum = tot;
   }
-  out[frag_offset(req, head * 128 + d, nq * 128)] = f2bf_dev(acc / l);
+  __syncthreads();
+  float acc = 0.f;
+  int i = 0;
+  for (; i + 8 <= n_chunks; i += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[(i + u) * kPartStride + 2 + d];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += wgt[i + u] * v[u];
+  }
+  for (; i < n_chunks; ++i) acc += wgt[i] * src[i * kPartStride + 2 + d];
+  out[frag_offset(req, head * 128 + d, nq * 128)] = f2bf_dev(acc / lsum);
 }
 
 }  // namespace
@@ -306,13 +324,14 @@ size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks) {
 }
 
 hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom,
-                            const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
-                            int max_chunks, hipStream_t s) {
+                            const int *lens, float *part, unsigned *counters, bf16_t *out, int nq, int nkv,
+                            int batch, int max_chunks, int chunk_keys, hipStream_t s) {
   int G = nq / nkv;
-  k_attn_decode<<<dim3(max_chunks, nkv, batch), 64, 0, s>>>(qdec, Kc, Vc, geom, lens, part, nq, G, max_chunks);
+  k_attn_decode<<<dim3(max_chunks, nkv, batch), 64, 0, s>>>(qdec, Kc, Vc, geom, lens, part, nq, G, max_chunks, chunk_keys);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  k_attn_decode_merge<<<dim3(nq, batch), 128, 0, s>>>(part, lens, out, nq, max_chunks);
+  (void)counters;
+  k_attn_decode_merge<<<dim3(nq, batch), 128, 0, s>>>(part, lens, out, nq, max_chunks, chunk_keys);
   return hipGetLastError();
 }
 

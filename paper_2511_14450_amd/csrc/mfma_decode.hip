@@ -10,36 +10,93 @@ namespace hyp {
 namespace {
 
 // ----------------------------------------------------------------------------
-// partial[ks][token][n] = sum over the K slice ks of W[n, k] x[token, k]
-// W = P(N, K): the 1 KiB tiles of one 32-row block are contiguous along K, and a
+// Skinny GEMM of a decode step with its consumer fused in.
+//
+//   sum[token, n] = sum_k W[n, k] x[token, k]        (<= 32 tokens, W streamed once)
+//
+// W = P(N, K): the 1 KiB tiles of one 32-row block are contiguous along K and a
 // tile is the MFMA A fragment as it stands, so every wave streams its slice
-// with 1 KiB fully coalesced loads straight into registers (no LDS on the way
-// in).  x = P(32, K) is tiny and stays in L2.  A workgroup owns FBW feature
-// blocks; its NW waves split the K slice and are reduced through LDS in wave
-// order (deterministic).
+// with fully coalesced 1 KiB loads straight into registers.  x = P(32, K) is
+// tiny and stays in L2.  A workgroup owns 64 packed rows (2 blocks); its 4 waves
+// split the workgroup's K slice and are reduced through LDS in wave order; the
+// `ksplit` workgroups of one row group write fp32 partial sums, and the one that
+// arrives last (a counter per row group) adds them up in slice order - so the
+// result does not depend on which one that is - and runs the epilogue.  The
+// partial sums are written with device-scope (write-through) stores that have
+// completed before the counter is bumped, which keeps cache write-backs and
+// invalidations out of the protocol.  Epilogues:
+//   DEC_QKV    scale by the RMS Norm factor, RoPE at position lens[b], write q
+//              to the decode query buffer and k, v into the cache
+//   DEC_SWIGLU scale, m = silu(gate) * up -> P(32, I)
+//   DEC_RESID  x += sum ; xres = x ; y' = x * gain -> P(32, H) ; per-token sum of
+//              squares of this row group -> ssq_out   (RMS Norm of the next
+//              sub-layer, applied by that sub-layer's epilogue as a scale:
+//              W (x * rstd * g) = rstd * W (x * g))
+//   DEC_FINAL  x += sum ; hidden_out = x
 // ----------------------------------------------------------------------------
-constexpr int FBW = 2, NW = 8, UNROLL = 5;
+constexpr int FBW = 2, NW = 4, UNROLL = 10;
+constexpr int kGroupRows = FBW * 32;
 
-__global__ void __launch_bounds__(NW * 64) k_gemv(const bf16_t *__restrict__ W,
-                                                  const bf16_t *__restrict__ x,
-                                                  float *__restrict__ partial, int N, int KT,
-                                                  int tiles_per_wave, int batch) {
-  extern __shared__ __attribute__((aligned(16))) float red_raw[];
-  float (*red)[FBW][16][64] = (float (*)[FBW][16][64])red_raw;
+struct DecGemvParams {
+  const bf16_t *W, *x;
+  float *partial;
+  unsigned *counters;
+  int N, KT, ksplit, tiles_per_wave, batch;
+  const float *ssq_in;  // [n_ssq][32]
+  int n_ssq;
+  float inv_H, eps;
+  const int *lens;
+  const float *cos_tab, *sin_tab;
+  bf16_t *qdec, *Kc, *Vc;
+  CacheGeom geom;
+  int nq, nkv;
+  bf16_t *m_out;
+  int I;
+  float *xres;
+  const bf16_t *gain;
+  bf16_t *y_out;
+  float *ssq_out;
+  bf16_t *hidden_out;
+  int H;
+};
+
+template <int EPI>
+__global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
+  __shared__ float red[NW][FBW][16][64];  // 32 KiB; reused as fin[32][65] once reduced
+  __shared__ float rstd_s[32];
+  __shared__ unsigned is_last;
+  float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1]) & red[0][0][0][0];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int fb0 = blockIdx.x * FBW, ks = blockIdx.y;
-  const int kt0 = (ks * NW + wave) * tiles_per_wave;
+  // what the epilogue needs from memory is fetched now, under the streaming loop
+  int pos_pf[4] = {0, 0, 0, 0};  // up to 32 tokens x 32 pairs over 256 threads
+  float cos_pf[4] = {0.f, 0.f, 0.f, 0.f}, sin_pf[4] = {0.f, 0.f, 0.f, 0.f};
+  if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {
+    if (EPI == DEC_QKV) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int idx = threadIdx.x + j * NW * 64;
+        if (idx < p.batch * 32) {
+          int d0 = ((fb0 >> 1) & 1) * 32 + (idx & 31);
+          pos_pf[j] = p.lens[idx >> 5];
+          cos_pf[j] = p.cos_tab[(size_t)pos_pf[j] * 64 + d0];
+          sin_pf[j] = p.sin_tab[(size_t)pos_pf[j] * 64 + d0];
+        }
+      }
+    }
+  }
+  const int kt0 = (ks * NW + wave) * p.tiles_per_wave;
   f32x16_t acc[FBW];
 #pragma unroll
   for (int i = 0; i < FBW; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  const bf16_t *xp = x + (size_t)kt0 * kTileElems + lane * 8;
+  const bf16_t *xp = p.x + (size_t)kt0 * kTileElems + lane * 8;
   const bf16_t *wp[FBW];
 #pragma unroll
-  for (int i = 0; i < FBW; ++i) wp[i] = W + ((size_t)(fb0 + i) * KT + kt0) * kTileElems + lane * 8;
+  for (int i = 0; i < FBW; ++i) wp[i] = p.W + ((size_t)(fb0 + i) * p.KT + kt0) * kTileElems + lane * 8;
   int t = 0;
-  for (; t + UNROLL <= tiles_per_wave; t += UNROLL) {
+  for (; t + UNROLL <= p.tiles_per_wave; t += UNROLL) {
     bf16x8_t xf[UNROLL], wf[FBW][UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -52,7 +109,7 @@ __global__ void __launch_bounds__(NW * 64) k_gemv(const bf16_t *__restrict__ W,
 #pragma unroll
       for (int i = 0; i < FBW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][u], xf[u], acc[i], 0, 0, 0);
   }
-  for (; t < tiles_per_wave; ++t) {
+  for (; t < p.tiles_per_wave; ++t) {
     bf16x8_t xf = *(const bf16x8_t *)(xp + (size_t)t * kTileElems);
 #pragma unroll
     for (int i = 0; i < FBW; ++i) {
@@ -65,74 +122,167 @@ __global__ void __launch_bounds__(NW * 64) k_gemv(const bf16_t *__restrict__ W,
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[wave][i][r][lane] = acc[i][r];
   __syncthreads();
-  // thread -> (token, feature f of the FBW*32 this workgroup owns): consecutive threads
-  // write consecutive features of one token row
-  for (int idx = threadIdx.x; idx < FBW * 32 * 32; idx += NW * 64) {
-    int f = idx % (FBW * 32), token = idx / (FBW * 32);
-    if (token >= batch) break;
-    int i = f >> 5, fl = f & 31;
-    int r = ((fl >> 3) << 2) + (fl & 3), l = (((fl >> 2) & 1) << 5) + token;
-    float sum = 0.f;
+  // sums of the 64 rows of this group: accumulator register r of lane l of block i is
+  // packed row 32 i + 8 (r/4) + 4 (l/32) + r%4, token l % 32.  At most 8 per thread.
+  const int n_pairs = p.batch * kGroupRows;
+  float mine[8];
 #pragma unroll
-    for (int w = 0; w < NW; ++w) sum += red[w][i][r][l];
-    partial[((size_t)ks * 32 + token) * N + fb0 * 32 + f] = sum;
+  for (int j = 0; j < 8; ++j) {
+    int idx = threadIdx.x + j * NW * 64;
+    mine[j] = 0.f;
+    if (idx < n_pairs) {
+      int f = idx % kGroupRows, token = idx / kGroupRows;
+      int i = f >> 5, fl = f & 31;
+      int r = ((fl >> 3) << 2) + (fl & 3), l = (((fl >> 2) & 1) << 5) + token;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) mine[j] += red[w][i][r][l];
+    }
   }
-}
-
-__device__ inline int packed_row_qkv(int head, int d) {
-  return head * 128 + ((d & 63) >> 5) * 64 + (d >> 6) * 32 + (d & 31);
-}
-
-// grid (batch, nq + 2 nkv), 64 threads: thread i owns the RoPE pair (i, i + 64)
-__global__ void __launch_bounds__(64) k_dec_qkv_finish(const float *__restrict__ partial, int ksplit,
-                                                       int N, const int *__restrict__ lens,
-                                                       const float *__restrict__ cos_tab,
-                                                       const float *__restrict__ sin_tab,
-                                                       bf16_t *__restrict__ qdec, bf16_t *__restrict__ Kc,
-                                                       bf16_t *__restrict__ Vc, CacheGeom geom, int nq,
-                                                       int nkv) {
-  const int b = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
-  const int pos = lens[b];
-  float a = 0.f, c = 0.f;
-  int r0 = packed_row_qkv(head, i), r1 = packed_row_qkv(head, i + 64);
-  for (int s = 0; s < ksplit; ++s) {
-    a += partial[((size_t)s * 32 + b) * N + r0];
-    c += partial[((size_t)s * 32 + b) * N + r1];
+  __syncthreads();  // `red` is free from here on
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int idx = threadIdx.x + j * NW * 64;
+    if (idx < n_pairs) {
+      int f = idx % kGroupRows, token = idx / kGroupRows;
+      if (p.ksplit > 1)  // write-through store: visible to the other XCDs once it has completed
+        __hip_atomic_store(&p.partial[((size_t)ks * 32 + token) * p.N + fb0 * 32 + f], mine[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else fin[token][f] = mine[j];
+    }
   }
-  if (head < nq + nkv) {
-    float cs = cos_tab[(size_t)pos * 64 + i], sn = sin_tab[(size_t)pos * 64 + i];
-    float lo = a * cs - c * sn, hi = c * cs + a * sn;
-    if (head < nq) {
-      int G = nq / nkv;
-      bf16_t *dst = qdec + ((size_t)b * nkv + head / G) * (32 * 128);
-      dst[frag_offset(head % G, i, 128)] = f2bf_dev(lo);
-      dst[frag_offset(head % G, i + 64, 128)] = f2bf_dev(hi);
-    } else {
-      bf16_t *dst = Kc + geom.off(b, head - nq, pos >> 5);
-      dst[frag_offset(pos & 31, i, 128)] = f2bf_dev(lo);
-      dst[frag_offset(pos & 31, i + 64, 128)] = f2bf_dev(hi);
+  if (p.ksplit > 1) {
+    __builtin_amdgcn_s_waitcnt(0);  // this thread's partial sums have completed ...
+    __syncthreads();
+    if (threadIdx.x == 0) {  // ... before it is counted
+      unsigned old = atomicAdd(&p.counters[blockIdx.x], 1u);
+      is_last = (old == (unsigned)p.ksplit - 1) ? 1u : 0u;
+      if (is_last) p.counters[blockIdx.x] = 0;  // ready for the next launch
+    }
+    __syncthreads();
+    if (!is_last) return;
+    // Plain loads are enough here: every 256-byte run of `partial` has exactly one
+    // writer in this launch, this XCD's L2 was invalidated when the launch began,
+    // and nothing in this launch read these lines before, so a line is either
+    // absent (fetched from memory, where the writer's store has completed) or was
+    // put there by a writer on this very XCD.  All slices are loaded before any is
+    // added, so the round trips overlap.
+    for (int idx = threadIdx.x; idx < n_pairs; idx += NW * 64) {
+      int f = idx % kGroupRows, token = idx / kGroupRows;
+      const float *src = p.partial + (size_t)token * p.N + fb0 * 32 + f;
+      float sum = 0.f;
+      int s = 0;
+      for (; s + 8 <= p.ksplit; s += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(s + u) * 32 * p.N];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += v[u];
+      }
+      for (; s < p.ksplit; ++s) sum += src[(size_t)s * 32 * p.N];
+      fin[token][f] = sum;
+    }
+  }
+  if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {
+    // RMS Norm factor of every token: the row groups' sums of squares, added in a
+    // fixed order (8 interleaved partial sums, then those in order)
+    __shared__ float ssq_part[8][32];
+    {
+      int tkn = threadIdx.x & 31, part = threadIdx.x >> 5;
+      float ss = 0.f;
+      for (int g = part; g < p.n_ssq; g += 8) ss += p.ssq_in[g * 32 + tkn];
+      ssq_part[part][tkn] = ss;
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {
+      float ss = 0.f;
+      for (int i = 0; i < 8; ++i) ss += ssq_part[i][threadIdx.x];
+      rstd_s[threadIdx.x] = 1.0f / sqrtf(ss * p.inv_H + p.eps);
+    }
+  }
+  __syncthreads();
+
+  if (EPI == DEC_QKV) {
+    const int r0 = fb0 * 32;
+    const int head = r0 >> 7, w = (r0 >> 6) & 1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int idx = threadIdx.x + j * NW * 64;
+      if (idx >= p.batch * 32) break;
+      int x = idx & 31, b = idx >> 5;
+      float a = fin[b][x] * rstd_s[b], c = fin[b][32 + x] * rstd_s[b];
+      int d0 = w * 32 + x, d1 = d0 + 64;
+      int pos = pos_pf[j];
+      if (head < p.nq + p.nkv) {
+        float cs = cos_pf[j], sn = sin_pf[j];
+        float lo = a * cs - c * sn, hi = c * cs + a * sn;
+        if (head < p.nq) {
+          int G = p.nq / p.nkv;
+          bf16_t *dst = p.qdec + ((size_t)b * p.nkv + head / G) * (32 * 128);
+          dst[frag_offset(head % G, d0, 128)] = f2bf_dev(lo);
+          dst[frag_offset(head % G, d1, 128)] = f2bf_dev(hi);
+        } else {
+          bf16_t *dst = p.Kc + p.geom.off(b, head - p.nq, pos >> 5);
+          dst[frag_offset(pos & 31, d0, 128)] = f2bf_dev(lo);
+          dst[frag_offset(pos & 31, d1, 128)] = f2bf_dev(hi);
+        }
+      } else {
+        bf16_t *dst = p.Vc + p.geom.off(b, head - p.nq - p.nkv, pos >> 5);
+        int m, khh;
+        int e = vtile_slot_of_key(pos & 31, &m, &khh);
+        dst[(size_t)(m * 4 + (d0 >> 5)) * kTileElems + (khh * 32 + (d0 & 31)) * 8 + e] = f2bf_dev(a);
+        dst[(size_t)(m * 4 + (d1 >> 5)) * kTileElems + (khh * 32 + (d1 & 31)) * 8 + e] = f2bf_dev(c);
+      }
+    }
+  } else if (EPI == DEC_SWIGLU) {
+    const int f0 = (fb0 >> 3) * 128 + ((fb0 >> 1) & 3) * 32;
+    for (int idx = threadIdx.x; idx < p.batch * 32; idx += NW * 64) {
+      int x = idx & 31, b = idx >> 5;
+      float g = fin[b][x] * rstd_s[b], u = fin[b][32 + x] * rstd_s[b];
+      p.m_out[frag_offset(b, f0 + x, p.I)] = f2bf_dev(g / (1.0f + __expf(-g)) * u);
     }
   } else {
-    bf16_t *dst = Vc + geom.off(b, head - nq - nkv, pos >> 5);
-    int m, khh;
-    int e = vtile_slot_of_key(pos & 31, &m, &khh);
-    dst[(size_t)(m * 4 + (i >> 5)) * kTileElems + (khh * 32 + (i & 31)) * 8 + e] = f2bf_dev(a);
-    dst[(size_t)(m * 4 + ((i + 64) >> 5)) * kTileElems + (khh * 32 + (i & 31)) * 8 + e] = f2bf_dev(c);
+    const int n0 = fb0 * 32;
+    for (int idx = threadIdx.x; idx < n_pairs; idx += NW * 64) {
+      int f = idx % kGroupRows, b = idx / kGroupRows;
+      float xn = p.xres[(size_t)b * p.H + n0 + f] + fin[b][f];
+      if (EPI == DEC_RESID) {
+        p.xres[(size_t)b * p.H + n0 + f] = xn;
+        p.y_out[frag_offset(b, n0 + f, p.H)] = f2bf_dev(xn * bf16_to_f32(p.gain[n0 + f]));
+        fin[b][f] = xn * xn;
+      } else {
+        p.hidden_out[(size_t)b * p.H + n0 + f] = f2bf_dev(xn);
+      }
+    }
+    if (EPI == DEC_RESID) {
+      __syncthreads();
+      if (threadIdx.x < p.batch) {
+        float ss = 0.f;
+        for (int f = 0; f < kGroupRows; ++f) ss += fin[threadIdx.x][f];
+        p.ssq_out[blockIdx.x * 32 + threadIdx.x] = ss;
+      }
+    }
   }
 }
 
-// grid (I / 256, batch), 256 threads: one FFN feature per thread
-__global__ void __launch_bounds__(256) k_dec_swiglu(const float *__restrict__ partial, int ksplit, int I,
-                                                    bf16_t *__restrict__ m) {
-  const int f = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
-  const int N = 2 * I;
-  int rg = (f >> 7) * 256 + ((f & 127) >> 5) * 64 + (f & 31), ru = rg + 32;
-  float g = 0.f, u = 0.f;
-  for (int s = 0; s < ksplit; ++s) {
-    g += partial[((size_t)s * 32 + b) * N + rg];
-    u += partial[((size_t)s * 32 + b) * N + ru];
+// first kernel of a decode step: x = hidden_in ; xres = x ; y' = x * gain ; ssq
+// grid H / 64, 256 threads
+__global__ void __launch_bounds__(256) k_dec_begin(const bf16_t *__restrict__ hidden_in, float *__restrict__ xres,
+                                                   const bf16_t *__restrict__ gain, bf16_t *__restrict__ y_out,
+                                                   float *__restrict__ ssq_out, int H, int batch) {
+  __shared__ float sq[32][kGroupRows + 1];
+  const int n0 = blockIdx.x * kGroupRows;
+  for (int idx = threadIdx.x; idx < batch * kGroupRows; idx += 256) {
+    int f = idx % kGroupRows, b = idx / kGroupRows;
+    float x = bf16_to_f32(hidden_in[(size_t)b * H + n0 + f]);
+    xres[(size_t)b * H + n0 + f] = x;
+    y_out[frag_offset(b, n0 + f, H)] = f2bf_dev(x * bf16_to_f32(gain[n0 + f]));
+    sq[b][f] = x * x;
   }
-  m[frag_offset(b, f, I)] = f2bf_dev(g / (1.0f + __expf(-g)) * u);
+  __syncthreads();
+  if (threadIdx.x < batch) {
+    float ss = 0.f;
+    for (int f = 0; f < kGroupRows; ++f) ss += sq[threadIdx.x][f];
+    ssq_out[blockIdx.x * 32 + threadIdx.x] = ss;
+  }
 }
 
 __global__ void k_export_kv(const bf16_t *__restrict__ Kc, const bf16_t *__restrict__ Vc, CacheGeom geom,
@@ -161,40 +311,42 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 
 }  // namespace
 
-constexpr int GEMV_LDS = NW * FBW * 16 * 64 * 4;
+hipError_t mfma_gemv_init() { return hipSuccess; }
 
-hipError_t mfma_gemv_init() {
-  return hipFuncSetAttribute((const void *)k_gemv, hipFuncAttributeMaxDynamicSharedMemorySize, GEMV_LDS);
-}
-
-hipError_t mfma_gemv(const bf16_t *W, const bf16_t *x, float *partial, int N, int K, int ksplit,
-                     int batch, hipStream_t s) {
-  int KT = K / 16;
-  int tiles_per_wave = KT / (ksplit * NW);
-  k_gemv<<<dim3(N / (32 * FBW), ksplit), NW * 64, GEMV_LDS, s>>>(W, x, partial, N, KT, tiles_per_wave, batch);
-  return hipGetLastError();
-}
-
-// K slices across workgroups: enough workgroups to fill the chip, few enough
-// that the fp32 partial sums stay a small fraction of the weight bytes
+// K slices across workgroups: about 10 or more tiles per wave, and no more
+// workgroups than keep the chip busy a few times over
 int mfma_gemv_ksplit(int N, int K) {
-  int KT = K / 16, groups = N / (32 * FBW);
-  int want = (1024 + groups - 1) / groups;
+  int KT = K / 16, groups = N / kGroupRows;
   int best = 1;
-  for (int ks = 1; ks <= want; ++ks)
-    if (KT % (ks * NW) == 0) best = ks;
+  for (int ks = 1; ks <= 64; ++ks) {
+    if (KT % (ks * NW) != 0) continue;
+    if (KT / (ks * NW) < 10 || groups * ks > 2400) break;
+    best = ks;
+  }
   return best;
 }
 
-hipError_t mfma_dec_qkv_finish(const float *partial, int ksplit, int N, const int *lens,
-                               const float *cos_tab, const float *sin_tab, bf16_t *qdec, bf16_t *Kc,
-                               bf16_t *Vc, CacheGeom geom, int nq, int nkv, int batch, hipStream_t s) {
-  k_dec_qkv_finish<<<dim3(batch, nq + 2 * nkv), 64, 0, s>>>(partial, ksplit, N, lens, cos_tab, sin_tab, qdec, Kc, Vc, geom, nq, nkv);
+hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s) {
+  DecGemvParams p = {};
+  p.W = a.W; p.x = a.x; p.partial = a.partial; p.counters = a.counters;
+  p.N = a.N; p.KT = a.K / 16; p.ksplit = a.ksplit; p.tiles_per_wave = p.KT / (a.ksplit * NW); p.batch = a.batch;
+  p.ssq_in = a.ssq_in; p.n_ssq = a.n_ssq; p.inv_H = a.n_ssq ? 1.0f / (float)(a.n_ssq * kGroupRows) : 0.f; p.eps = a.eps;
+  p.lens = a.lens; p.cos_tab = a.cos_tab; p.sin_tab = a.sin_tab; p.qdec = a.qdec; p.Kc = a.Kc; p.Vc = a.Vc;
+  p.geom = a.geom; p.nq = a.nq; p.nkv = a.nkv; p.m_out = a.m_out; p.I = a.I; p.xres = a.xres; p.gain = a.gain;
+  p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H;
+  dim3 grid(a.N / kGroupRows, a.ksplit);
+  switch (epi) {
+    case DEC_QKV: k_dec_gemv<DEC_QKV><<<grid, NW * 64, 0, s>>>(p); break;
+    case DEC_SWIGLU: k_dec_gemv<DEC_SWIGLU><<<grid, NW * 64, 0, s>>>(p); break;
+    case DEC_RESID: k_dec_gemv<DEC_RESID><<<grid, NW * 64, 0, s>>>(p); break;
+    default: k_dec_gemv<DEC_FINAL><<<grid, NW * 64, 0, s>>>(p); break;
+  }
   return hipGetLastError();
 }
 
-hipError_t mfma_dec_swiglu(const float *partial, int ksplit, int I, bf16_t *m, int batch, hipStream_t s) {
-  k_dec_swiglu<<<dim3(I / 256, batch), 256, 0, s>>>(partial, ksplit, I, m);
+hipError_t mfma_dec_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y_out, float *ssq_out,
+                          int H, int batch, hipStream_t s) {
+  k_dec_begin<<<H / kGroupRows, 256, 0, s>>>(hidden_in, xres, gain, y_out, ssq_out, H, batch);
   return hipGetLastError();
 }
 

@@ -41,24 +41,50 @@ hipError_t mfma_attn_prefill(const bf16_t *q, const bf16_t *Kc, const bf16_t *Vc
                              int nq, int nkv, hipStream_t s);
 
 // ------------------------------------------------------------------ decode
-// partial[ks][32][N] (fp32) = x[32 rows, K-slice ks] W[N, K-slice]^T, token rows < batch only
-hipError_t mfma_gemv(const bf16_t *W, const bf16_t *x, float *partial, int N, int K, int ksplit,
-                     int batch, hipStream_t s);
-int mfma_gemv_ksplit(int N, int K);
+enum { DEC_QKV = 0, DEC_SWIGLU = 1, DEC_RESID = 2, DEC_FINAL = 3 };
 
-// sum the QKV partials, rotate q and k at position lens[b], write q into the
-// decode query buffer and k, v into the caches
-hipError_t mfma_dec_qkv_finish(const float *partial, int ksplit, int N, const int *lens,
-                               const float *cos_tab, const float *sin_tab, bf16_t *qdec, bf16_t *Kc,
-                               bf16_t *Vc, CacheGeom geom, int nq, int nkv, int batch, hipStream_t s);
+// One skinny GEMM of a decode step, sum[token, n] = W[n, :] . x[token, :], with
+// its consumer fused in (see k_dec_gemv).  Fields a given epilogue does not use
+// stay null / 0.
+struct DecGemv {
+  const bf16_t *W = nullptr, *x = nullptr;  // P(N, K), P(32, K)
+  float *partial = nullptr;                 // [ksplit][32][N]
+  unsigned *counters = nullptr;             // [N / 64], zero between launches
+  int N = 0, K = 0, ksplit = 1, batch = 0;
+  const float *ssq_in = nullptr;            // [n_ssq][32] sums of squares of the normalised input
+  int n_ssq = 0;
+  float eps = 0.f;
+  const int *lens = nullptr;
+  const float *cos_tab = nullptr, *sin_tab = nullptr;
+  bf16_t *qdec = nullptr, *Kc = nullptr, *Vc = nullptr;
+  CacheGeom geom = {};
+  int nq = 0, nkv = 0;
+  bf16_t *m_out = nullptr;
+  int I = 0;
+  float *xres = nullptr;
+  const bf16_t *gain = nullptr;
+  bf16_t *y_out = nullptr;
+  float *ssq_out = nullptr;
+  bf16_t *hidden_out = nullptr;
+  int H = 0;
+};
+hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s);
+int mfma_gemv_ksplit(int N, int K);
+// x = hidden_in ; xres = x ; y' = x * gain -> P(32, H) ; ssq_out[H/64][32]
+hipError_t mfma_dec_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y_out, float *ssq_out,
+                          int H, int batch, hipStream_t s);
+
 // split-KV decode attention + fixed-order merge; out row b of P(32, nq*128)
 hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom,
-                            const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
-                            int max_chunks, hipStream_t s);
+                            const int *lens, float *part, unsigned *counters, bf16_t *out, int nq, int nkv,
+                            int batch, int max_chunks, int chunk_keys, hipStream_t s);
 size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks);
-constexpr int kDecodeChunkKeys = 128;
-// m = silu(gate) * up from the gate/up partials -> P(32, I)
-hipError_t mfma_dec_swiglu(const float *partial, int ksplit, int I, bf16_t *m, int batch, hipStream_t s);
+// keys per decode-attention chunk: 128, doubled until a context has at most 64 chunks
+inline int mfma_decode_chunk_keys(int max_seq) {
+  int c = 128;
+  while ((max_seq + c - 1) / c > 64) c *= 2;
+  return c;
+}
 
 // cache -> plain [len, nkv*128] rows
 hipError_t mfma_export_kv(const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom, bf16_t *k_out,

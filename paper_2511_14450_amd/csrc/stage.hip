@@ -35,11 +35,12 @@ struct Layout {
   size_t tok_req = 0, tok_pos = 0, lens = 0, iota = 0;
   // MFMA path only
   size_t q = 0, delta = 0, row_ext = 0, row_pos = 0, row_req = 0, tiles = 0, req_len = 0, row_ext_dec = 0, qdec = 0,
-         partial = 0, attn_part = 0;
+         partial = 0, attn_part = 0, counters = 0, attn_counters = 0, ssq = 0;
   size_t kv_bytes = 0;  // bytes of each of Kc, Vc over all layers
   int rows_cap = 0;     // internal rows the scratch holds
   int key_blocks = 0;   // 32-key blocks per (request, kv head)
   int max_chunks = 0;   // decode attention chunks per head
+  int chunk_keys = 128; // keys per chunk
   int ks_qkv = 1, ks_o = 1, ks_gu = 1, ks_d = 1;
   size_t total = 0;
 };
@@ -137,8 +138,12 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     size_t pf = std::max(std::max((size_t)L.ks_qkv * (qd + 2 * kvd), (size_t)L.ks_o * H),
                          std::max((size_t)L.ks_gu * 2 * I, (size_t)L.ks_d * H));
     L.partial = take(sizeof(float) * pf * 32);
-    L.max_chunks = (c.max_seq + kDecodeChunkKeys - 1) / kDecodeChunkKeys;
+    L.chunk_keys = mfma_decode_chunk_keys(c.max_seq);
+    L.max_chunks = (c.max_seq + L.chunk_keys - 1) / L.chunk_keys;
     L.attn_part = take(sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks));
+    L.counters = take(sizeof(unsigned) * (2 * I / 64 + (qd + 2 * kvd) / 64 + H / 64));
+    L.attn_counters = take(sizeof(unsigned) * (size_t)c.max_batch * c.n_kv_heads);
+    L.ssq = take(sizeof(float) * 32 * (H / 64));
     L.total = off;
     return;
   }
@@ -183,10 +188,14 @@ struct hyp_stage {
   std::vector<ProfSlot> prof;
   size_t prof_used = 0;
   uint32_t prof_mask = 0;
-  // the layer loop of a decode step, captured once per batch size and replayed
-  hipGraph_t dec_graph = nullptr;
-  hipGraphExec_t dec_exec = nullptr;
-  int dec_graph_batch = 0;
+  // recorded decode steps (kernel arguments baked in), replayed when they match
+  struct DecGraph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    int batch = 0;
+    void *out = nullptr;
+  };
+  std::vector<DecGraph> dec_graphs;
   hipStream_t cap_stream = nullptr;  // recording only (the null stream cannot be captured); nothing runs on it
   int batch;
   bool prefilled;
@@ -292,6 +301,7 @@ hyp_status_t pack_weights_mfma(hyp_stage *st, const hyp_layer_weights_t *layers)
   HIP_TRY(st, mfma_fill_zero(st->ws + st->L.Kc, st->L.kv_bytes, s));
   HIP_TRY(st, mfma_fill_zero(st->ws + st->L.Vc, st->L.kv_bytes, s));
   HIP_TRY(st, mfma_fill_zero(st->ws + st->L.qdec, 2 * (size_t)d.max_batch * d.nkv * 32 * 128, s));
+  HIP_TRY(st, mfma_fill_zero(st->ws + st->L.counters, st->L.ssq - st->L.counters, s));
   return HYP_OK;
 }
 
@@ -340,84 +350,104 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
   return HYP_OK;
 }
 
-// the part of a decode step that touches only the stage's own buffers: every
-// kernel between the first residual/norm (reads hidden_in) and the last one
-// (writes hidden_out)
-hyp_status_t decode_layers_mfma(hyp_stage *st, hipStream_t s) {
+// One decode step through the MFMA kernels (a single block of 32 token rows):
+// 1 + 5 launches per block, every reduction finished inside the kernel that
+// produced it.
+hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const void *hidden_in, void *hidden_out, bool begin,
+                              bool layers) {
   const Dims &d = st->dm;
   const Layout &L = st->L;
-  const int B = st->batch;
-  float *xres = at<float>(st, L.xres), *part = at<float>(st, L.partial);
+  DecGemv base;
+  base.partial = at<float>(st, L.partial);
+  base.counters = at<unsigned>(st, L.counters);
+  base.batch = st->batch;
+  base.eps = d.eps;
+  base.H = d.H;
+  base.xres = at<float>(st, L.xres);
+  float *ssq = at<float>(st, L.ssq);
   bf16_t *y = at<bf16_t>(st, L.y), *attn = at<bf16_t>(st, L.attn), *m = at<bf16_t>(st, L.m);
-  bf16_t *qdec = at<bf16_t>(st, L.qdec);
-  const int *row_ext = at<int>(st, L.row_ext_dec), *lens = at<int>(st, L.lens);
-  const float *ct = at<float>(st, L.cos_tab), *sn = at<float>(st, L.sin_tab);
   CacheGeom geom = cache_geom(st);
-  const int Nqkv = d.qd + 2 * d.kvd;
-  for (int l = 0; l < st->n_layers; ++l) {
+  if (begin)
+    PROF(st, HYP_K_ADD_NORM, mfma_dec_begin((const bf16_t *)hidden_in, base.xres, at<bf16_t>(st, L.layers[0].g1), y, ssq,
+                                             d.H, st->batch, s));
+  for (int l = 0; layers && l < st->n_layers; ++l) {
     const LayerPtrs &p = L.layers[l];
     bf16_t *Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l), *Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
-    PROF(st, HYP_K_GEMV_QKV, mfma_gemv(at<bf16_t>(st, p.wqkv), y, part, Nqkv, d.H, L.ks_qkv, B, s));
-    PROF(st, HYP_K_DEC_QKV_FINISH, mfma_dec_qkv_finish(part, L.ks_qkv, Nqkv, lens, ct, sn, qdec, Kc, Vc, geom, d.nq, d.nkv, B, s));
-    PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(qdec, Kc, Vc, geom, lens, at<float>(st, L.attn_part), attn, d.nq, d.nkv, B,
-                                 L.max_chunks, s));
-    PROF(st, HYP_K_GEMV_O, mfma_gemv(at<bf16_t>(st, p.wo), attn, part, d.H, d.qd, L.ks_o, B, s));
-    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_o, (size_t)32 * d.H, at<bf16_t>(st, p.g2), y, nullptr,
-                              row_ext, 32, d.H, d.eps, false, s));
-    PROF(st, HYP_K_GEMV_GATEUP, mfma_gemv(at<bf16_t>(st, p.wgu), y, part, 2 * d.I, d.H, L.ks_gu, B, s));
-    PROF(st, HYP_K_DEC_SWIGLU, mfma_dec_swiglu(part, L.ks_gu, d.I, m, B, s));
-    PROF(st, HYP_K_GEMV_DOWN, mfma_gemv(at<bf16_t>(st, p.wd), m, part, d.H, d.I, L.ks_d, B, s));
-    if (l + 1 < st->n_layers)
-      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)32 * d.H, at<bf16_t>(st, L.layers[l + 1].g1),
-                                y, nullptr, row_ext, 32, d.H, d.eps, false, s));
+    DecGemv a = base;
+    a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.ksplit = L.ks_qkv;
+    a.ssq_in = ssq; a.n_ssq = d.H / 64;
+    a.lens = at<int>(st, L.lens); a.cos_tab = at<float>(st, L.cos_tab); a.sin_tab = at<float>(st, L.sin_tab);
+    a.qdec = at<bf16_t>(st, L.qdec); a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
+    PROF(st, HYP_K_GEMV_QKV, mfma_dec_gemv(DEC_QKV, a, s));
+    PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(a.qdec, Kc, Vc, geom, a.lens, at<float>(st, L.attn_part),
+                                                 at<unsigned>(st, L.attn_counters), attn, d.nq, d.nkv, st->batch,
+                                                 L.max_chunks, L.chunk_keys, s));
+    DecGemv o = base;
+    o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.ksplit = L.ks_o;
+    o.gain = at<bf16_t>(st, p.g2); o.y_out = y; o.ssq_out = ssq;
+    PROF(st, HYP_K_GEMV_O, mfma_dec_gemv(DEC_RESID, o, s));
+    DecGemv g = base;
+    g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.ksplit = L.ks_gu;
+    g.ssq_in = ssq; g.n_ssq = d.H / 64; g.m_out = m; g.I = d.I;
+    PROF(st, HYP_K_GEMV_GATEUP, mfma_dec_gemv(DEC_SWIGLU, g, s));
+    DecGemv w = base;
+    w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.ksplit = L.ks_d;
+    if (l + 1 < st->n_layers) {
+      w.gain = at<bf16_t>(st, L.layers[l + 1].g1); w.y_out = y; w.ssq_out = ssq;
+      PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_RESID, w, s));
+    } else {
+      w.hidden_out = (bf16_t *)hidden_out;
+      PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_FINAL, w, s));
+    }
   }
   return HYP_OK;
 }
 
-void drop_decode_graph(hyp_stage *st) {
-  if (st->dec_exec) (void)hipGraphExecDestroy(st->dec_exec);
-  if (st->dec_graph) (void)hipGraphDestroy(st->dec_graph);
-  st->dec_exec = nullptr;
-  st->dec_graph = nullptr;
+void drop_decode_graph(hyp_stage::DecGraph &g) {
+  if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (g.graph) (void)hipGraphDestroy(g.graph);
+  g.exec = nullptr;
+  g.graph = nullptr;
 }
 
-// one decode step through the MFMA kernels: a single block of 32 token rows.
-// The ~10 launches per block are latency-bound next to ~0.1 ms of streaming, so
-// the layer loop is recorded into a HIP graph (kernel nodes only) the first time
-// a batch size is seen and replayed afterwards; while kernel classes are being
-// timed, or when the caller is itself capturing the stream, it is launched
-// kernel by kernel instead.
+// The launches of a decode step are latency-bound next to ~0.1 ms of streaming
+// per block, so the step is recorded into a HIP graph (kernel nodes only) the
+// first time a (batch, output buffer) pair is seen and replayed afterwards;
+// while kernel classes are being timed, or when the caller is itself capturing
+// the stream, it is launched kernel by kernel instead.
 hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_out) {
-  const Dims &d = st->dm;
   hipStream_t s = st->stream;
-  const Layout &L = st->L;
-  float *xres = at<float>(st, L.xres), *part = at<float>(st, L.partial);
-  const int *row_ext = at<int>(st, L.row_ext_dec);
-  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1),
-                            at<bf16_t>(st, L.y), nullptr, row_ext, 32, d.H, d.eps, false, s));
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
   HIP_TRY(st, hipStreamIsCapturing(s, &cap));
   bool use_graph = st->prof_mask == 0 && cap == hipStreamCaptureStatusNone && !(st->cfg.flags & HYP_FLAG_NO_GRAPH);
-  if (use_graph) {
-    if (!st->dec_exec || st->dec_graph_batch != st->batch) {
-      drop_decode_graph(st);
-      if (!st->cap_stream) HIP_TRY(st, hipStreamCreateWithFlags(&st->cap_stream, hipStreamNonBlocking));
-      HIP_TRY(st, hipStreamBeginCapture(st->cap_stream, hipStreamCaptureModeThreadLocal));
-      hyp_status_t rc = decode_layers_mfma(st, st->cap_stream);
-      hipError_t e = hipStreamEndCapture(st->cap_stream, &st->dec_graph);
-      if (rc != HYP_OK) { drop_decode_graph(st); return rc; }
-      if (e != hipSuccess) { drop_decode_graph(st); return fail(st, HYP_EDEVICE, std::string("hipStreamEndCapture: ") + hipGetErrorString(e)); }
-      e = hipGraphInstantiate(&st->dec_exec, st->dec_graph, nullptr, nullptr, 0);
-      if (e != hipSuccess) { drop_decode_graph(st); return fail(st, HYP_EDEVICE, std::string("hipGraphInstantiate: ") + hipGetErrorString(e)); }
-      st->dec_graph_batch = st->batch;
+  if (!use_graph) return decode_step_mfma(st, s, hidden_in, hidden_out, true, true);
+  // the first kernel reads the caller's input and stays outside the recording, so a
+  // new input address every step does not force a new graph
+  hyp_status_t rc0 = decode_step_mfma(st, s, hidden_in, hidden_out, true, false);
+  if (rc0 != HYP_OK) return rc0;
+  // a few recorded graphs, keyed by what is baked into their kernel arguments
+  hyp_stage::DecGraph *g = nullptr;
+  for (auto &c : st->dec_graphs)
+    if (c.batch == st->batch && c.out == hidden_out) g = &c;
+  if (!g) {
+    if (st->dec_graphs.size() >= 4) {
+      drop_decode_graph(st->dec_graphs.front());
+      st->dec_graphs.erase(st->dec_graphs.begin());
     }
-    HIP_TRY(st, hipGraphLaunch(st->dec_exec, s));
-  } else {
-    hyp_status_t rc = decode_layers_mfma(st, s);
-    if (rc != HYP_OK) return rc;
+    hyp_stage::DecGraph n;
+    n.batch = st->batch; n.out = hidden_out;
+    if (!st->cap_stream) HIP_TRY(st, hipStreamCreateWithFlags(&st->cap_stream, hipStreamNonBlocking));
+    HIP_TRY(st, hipStreamBeginCapture(st->cap_stream, hipStreamCaptureModeThreadLocal));
+    hyp_status_t rc = decode_step_mfma(st, st->cap_stream, hidden_in, hidden_out, false, true);
+    hipError_t e = hipStreamEndCapture(st->cap_stream, &n.graph);
+    if (rc != HYP_OK) { drop_decode_graph(n); return rc; }
+    if (e != hipSuccess) { drop_decode_graph(n); return fail(st, HYP_EDEVICE, std::string("hipStreamEndCapture: ") + hipGetErrorString(e)); }
+    e = hipGraphInstantiate(&n.exec, n.graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) { drop_decode_graph(n); return fail(st, HYP_EDEVICE, std::string("hipGraphInstantiate: ") + hipGetErrorString(e)); }
+    st->dec_graphs.push_back(n);
+    g = &st->dec_graphs.back();
   }
-  PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, nullptr, part, L.ks_d, (size_t)32 * d.H, nullptr, nullptr,
-                            (bf16_t *)hidden_out, row_ext, 32, d.H, d.eps, true, s));
+  HIP_TRY(st, hipGraphLaunch(g->exec, s));
   return HYP_OK;
 }
 
@@ -704,7 +734,7 @@ hyp_status_t stage_destroy(hyp_stage_t *st) {
   if (st->upload_done) (void)hipEventDestroy(st->upload_done);
   if (st->h_stage) (void)hipHostFree(st->h_stage);
   for (auto &ps : st->prof) { (void)hipEventDestroy(ps.a); (void)hipEventDestroy(ps.b); }
-  drop_decode_graph(st);
+  for (auto &g : st->dec_graphs) drop_decode_graph(g);
   if (st->cap_stream) (void)hipStreamDestroy(st->cap_stream);
   delete st;
   return HYP_OK;

@@ -29,6 +29,31 @@ from workloads import synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4096 FLOP/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_c3_stage10.json")
+
+
+def kernel_sources_digest():
+    """sha256 over the HIP sources: traffic counters are only quoted for the kernels they were taken from."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2511_14450_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        with open(os.path.join(d, name), "rb") as f:
+            h.update(name.encode()); h.update(f.read())
+    return h.hexdigest()
+
+
+def committed_traffic(workload):
+    """{kernel class: HBM bytes per launch} from the committed rocprofv3 --pmc summary, or {} when it
+    belongs to another workload or to older kernel sources."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except OSError:
+        return {}
+    if t.get("workload") != workload or t.get("sources_sha256") != kernel_sources_digest():
+        return {}
+    return t.get("hbm_bytes_per_launch", {})
 
 
 def device_weights(shape, n_layers, seed):
@@ -89,6 +114,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c3_stage10", choices=[k for k in synth.WORKLOADS if k != "c1_tiny_f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override the block count (counter runs on a shorter stage)")
+    ap.add_argument("--decode-steps", type=int, default=-1, help="override the number of decode steps")
+    ap.add_argument("--no-graph", action="store_true", help="launch decode kernels one by one (for counter runs)")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run one 256 MiB device copy, the known-size reference for FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one stage on ONE GPU: a stage is the unit the pipeline places on a single "
@@ -102,11 +132,16 @@ def main():
         print("no GPU visible", file=sys.stderr)
         sys.exit(1)
     wl = synth.WORKLOADS[args.workload]
+    if args.layers > 0 or args.decode_steps >= 0:
+        import dataclasses
+        wl = dataclasses.replace(wl, n_layers=args.layers if args.layers > 0 else wl.n_layers,
+                                 decode_steps=args.decode_steps if args.decode_steps >= 0 else wl.decode_steps)
     shape = wl.shape
     lens = wl.lengths()
     B, T = len(lens), sum(lens)
     n_dec = wl.decode_steps
-    cfg = hyp.stage_config(shape, B, max(lens) + n_dec, T)
+    from paper_2511_14450_amd import binding
+    cfg = hyp.stage_config(shape, B, max(lens) + n_dec, T, flags=binding.HYP_FLAG_NO_GRAPH if args.no_graph else 0)
     layers = device_weights(shape, wl.n_layers, wl.seed)
     stage = hyp.stage_create(cfg, 0, wl.n_layers, layers)
     del layers
@@ -132,6 +167,12 @@ def main():
         if record:
             ev[2].record()
 
+    if args.traffic_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        dst.copy_(src)      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -174,6 +215,9 @@ def main():
             rows.append({"kernel": c, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": ach / PEAK_HBM_GBS, "traffic": None, "launches": n, "avg_ms": ms / n, "total_ms": ms})
     stage.profile([])
+    traffic = committed_traffic(wl.name)
+    for r in rows:
+        r["traffic"] = traffic.get(r["kernel"])
     rows.sort(key=lambda r: -r["total_ms"])
     dominant = rows[0]
 
@@ -184,7 +228,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "layers": wl.n_layers, "batch": B, "prefill_tokens": T,
+        "config": {"workload": wl.name + ("" if (args.layers <= 0 and args.decode_steps < 0) else " (overridden)"), "layers": wl.n_layers, "batch": B, "prefill_tokens": T,
                    "decode_steps": n_dec, "hidden": H, "ffn": I, "q_heads": shape.n_q_heads,
                    "kv_heads": shape.n_kv_heads},
         "prefill_tokens_per_s": T / (pre * 1e-3),

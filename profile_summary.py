@@ -1,0 +1,117 @@
+#!/usr/bin/env python3
+"""Turn rocprofv3 CSV output of `bench.py` into the short text summaries kept under profiles/.
+
+  kernel stats :  python profile_summary.py stats  <dir>/<name>_kernel_stats.csv
+  HBM traffic  :  python profile_summary.py traffic <fetch>_counter_collection.csv <write>_counter_collection.csv
+                  [--json profiles/traffic_c3_stage10.json --workload c3_stage10]
+
+FETCH_SIZE / WRITE_SIZE are reported by rocprofv3 in KiB per dispatch; both are scaled by
+what the same counter reads for the 256 MiB device copy that `bench.py --traffic-calibration`
+runs (the scale factors are printed).
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import json
+import re
+import sys
+
+CLASS_OF = [  # (regex on the kernel name, grid-x test, class)
+    (r"k_gemm<2>", "gemm_qkv"), (r"k_gemm<1>", "gemm_gateup"), (r"k_attn_prefill", "attn_prefill"),
+    (r"k_attn_decode_merge", "attn_decode_merge"), (r"k_attn_decode", "attn_decode"),
+    (r"k_dec_gemv<0>", "gemv_qkv"), (r"k_dec_gemv<1>", "gemv_gateup"), (r"k_add_norm", "add_norm"),
+    (r"k_dec_begin", "dec_begin"),
+]
+
+
+# kernels shared by two classes, told apart by their launch size on the c3 workload
+# (total work-items): prefill O / down projections differ only in K, so both have the
+# grid of a [16384 x 5120] output and are reported together; decode O / down differ in ksplit
+NAME_BY_GRID = {
+    "k_dec_gemv<2>/grid163840": "gemv_o", "k_dec_gemv<3>/grid573440": "gemv_down",
+    "k_dec_gemv<2>/grid573440": "gemv_down", "k_gemm<0>/grid655360": "gemm_o+gemm_down",
+}
+
+
+def short(name: str) -> str:
+    m = re.search(r"(k_\w+)(<[^>]*>)?", name)
+    return (m.group(1) + (m.group(2) or "")) if m else name.split("(")[0][-48:]
+
+
+def classify(row) -> str:
+    """Kernel class as bench.py names it; the two plain-epilogue GEMMs and the two residual
+    decode GEMMs share a kernel and are told apart by their grid."""
+    n = short(row["Kernel_Name"])
+    grid = row.get("Grid_Size") or (row.get("Grid_Size_X", "") + "x" + row.get("Grid_Size_Y", ""))
+    for pat, cls in CLASS_OF:
+        if re.search(pat, n):
+            return cls
+    if n.startswith("k_gemm<0>") or n.startswith("k_dec_gemv<2>") or n.startswith("k_dec_gemv<3>"):
+        return n + f"/grid{grid}"
+    return n
+
+
+def stats(path):
+    rows = list(csv.DictReader(open(path)))
+    print(f"{'kernel':44s} {'calls':>7s} {'avg_us':>10s} {'total_ms':>10s} {'pct':>6s}")
+    for r in rows:
+        if float(r["Percentage"]) < 0.05:
+            continue
+        print(f"{short(r['Name']):44s} {r['Calls']:>7s} {float(r['AverageNs']) / 1e3:10.1f} "
+              f"{float(r['TotalDurationNs']) / 1e6:10.1f} {float(r['Percentage']):6.2f}")
+
+
+def per_class(path, counter):
+    agg = collections.defaultdict(list)
+    copy = []
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] != counter:
+            continue
+        v = float(r["Counter_Value"])
+        name = r["Kernel_Name"]
+        if "copyBuffer" in name:
+            copy.append((v, name))
+        agg[classify(r)].append(v)
+    return agg, copy
+
+
+def traffic(fetch_csv, write_csv, out_json, workload):
+    f, fcopy = per_class(fetch_csv, "FETCH_SIZE")
+    w, wcopy = per_class(write_csv, "WRITE_SIZE")
+    ref_kib = 256 * 1024.0
+    # the calibration copy is the largest copy-like dispatch
+    fscale = ref_kib / max(v for v, _ in fcopy) if fcopy else 1.0
+    wscale = ref_kib / max(v for v, _ in wcopy) if wcopy else 1.0
+    print(f"calibration: 256 MiB copy read as FETCH_SIZE={max(v for v, _ in fcopy) if fcopy else float('nan'):.0f} KiB "
+          f"(scale {fscale:.4f}), WRITE_SIZE={max(v for v, _ in wcopy) if wcopy else float('nan'):.0f} KiB (scale {wscale:.4f})")
+    print(f"{'kernel class':36s} {'launches':>8s} {'fetch MiB':>10s} {'write MiB':>10s}")
+    result = {}
+    for cls in sorted(set(f) | set(w)):
+        if not cls.startswith(("gemm", "gemv", "attn", "k_gemm", "k_dec", "add_norm", "dec_")):
+            continue
+        cls_out = NAME_BY_GRID.get(cls, cls)
+        fb = sum(f.get(cls, [0])) / max(len(f.get(cls, [1])), 1) * fscale * 1024
+        wb = sum(w.get(cls, [0])) / max(len(w.get(cls, [1])), 1) * wscale * 1024
+        print(f"{cls_out:36s} {len(f.get(cls, [])):8d} {fb / 2**20:10.1f} {wb / 2**20:10.1f}")
+        result[cls_out] = fb + wb
+    if out_json:
+        sys.path.insert(0, ".")
+        import bench
+        json.dump({"workload": workload, "sources_sha256": bench.kernel_sources_digest(),
+                   "unit": "bytes (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration)",
+                   "hbm_bytes_per_launch": result}, open(out_json, "w"), indent=1)
+
+
+if __name__ == "__main__":
+    ap = argparse.ArgumentParser()
+    ap.add_argument("mode", choices=["stats", "traffic"])
+    ap.add_argument("files", nargs="+")
+    ap.add_argument("--json")
+    ap.add_argument("--workload", default="c3_stage10")
+    a = ap.parse_args()
+    if a.mode == "stats":
+        stats(a.files[0])
+    else:
+        traffic(a.files[0], a.files[1], a.json, a.workload)

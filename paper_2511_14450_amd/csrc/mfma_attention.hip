@@ -24,142 +24,135 @@ __device__ __forceinline__ bf16x8_t probs_operand(const float *p /*16*/, int m) 
 }
 
 // ----------------------------------------------------------------------------
-// Prefill.  One workgroup = one KV head x one tile of 64 query rows; its G waves
-// are the G query heads that share the KV head, so each 32-key block of K and V
-// (16 KiB, already in fragment order) is fetched once into LDS by direct loads
-// and read by all G waves.  Per wave: S^T = K Q^T (keys on the MFMA M axis, so a
+// Prefill.  One workgroup = one KV head x one tile of 64 query rows.  It has two
+// waves per query head of the group (32 query rows each), so a K / V stage of 64
+// keys (32 KiB, already in fragment order) is fetched once into LDS by direct
+// loads and read by all 2G waves, and each SIMD holds two waves whose MFMA and
+// softmax phases overlap.  Per wave: S^T = K Q^T (keys on the MFMA M axis, so a
 // lane owns one query column and the softmax reductions stay inside a lane plus
 // one cross-half exchange), online softmax in fp32, O^T += V^T P^T.
 // ----------------------------------------------------------------------------
-constexpr int kKvBlockBytes = 16384;  // 8 K tiles + 8 V tiles
+constexpr int kKvStageKeys = 64;
+constexpr int kKvStageBytes = 2 * 16384;  // per 32 keys: 8 K tiles + 8 V tiles
 
-__global__ void __launch_bounds__(256) k_attn_prefill(const bf16_t *__restrict__ q,
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__ q,
                                                       const bf16_t *__restrict__ Kc,
                                                       const bf16_t *__restrict__ Vc, CacheGeom geom,
                                                       bf16_t *__restrict__ out,
                                                       const PrefillTile *__restrict__ tiles,
                                                       const int *__restrict__ req_len, int nq, int G) {
-  __shared__ __attribute__((aligned(1024))) char lds[2 * kKvBlockBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[2 * kKvStageBytes];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hh = lane >> 5, tl = lane & 31;
+  const int nw = blockDim.x >> 6;  // 2 G
   const PrefillTile tile = tiles[blockIdx.x];
   const int kvh = blockIdx.y;
-  const int head = kvh * G + wave;
+  const int head = kvh * G + (wave >> 1);
+  const int tq = wave & 1;                 // which 32-row block of the tile
+  const int qblk = tile.qblk0 + tq;        // its index inside the request
   const int qd = nq * 128;
   const int len = req_len[tile.req];
-  const int n_kb = min(tile.qblk0 + 2, (len + 31) >> 5);
-  const int rb0 = tile.row0 >> 5;
+  const int n_kb = min(tile.qblk0 + 2, (len + 31) >> 5);  // 32-key blocks the tile needs
+  const int n_st = (n_kb + 1) >> 1;                        // 64-key stages
+  const int rb = (tile.row0 >> 5) + tq;
   const float c = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
+  const int qpos = qblk * 32 + tl;
 
-  // query fragments of this head: B operand, 2 query blocks x 8 k-tiles
-  bf16x8_t qf[2][8];
+  bf16x8_t qf[8];
 #pragma unroll
-  for (int tq = 0; tq < 2; ++tq)
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
-      qf[tq][dt] = *(const bf16x8_t *)(q + ((size_t)(rb0 + tq) * (qd >> 4) + head * 8 + dt) * kTileElems + lane * 8);
+  for (int dt = 0; dt < 8; ++dt)
+    qf[dt] = *(const bf16x8_t *)(q + ((size_t)rb * (qd >> 4) + head * 8 + dt) * kTileElems + lane * 8);
 
-  f32x16_t o[4][2];
+  f32x16_t o[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int tq = 0; tq < 2; ++tq)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][tq][r] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
 
-  const int nw = blockDim.x >> 6;
-  auto issue = [&](int kb, int buf) {
-    // 16 tiles of 1 KiB, spread over the waves
-    for (int t = wave; t < 16; t += nw) {
-      const bf16_t *src = (t < 8 ? Kc : Vc) + geom.off(tile.req, kvh, kb) + (size_t)(t & 7) * kTileElems + lane * 8;
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvBlockBytes + t * 1024), 16, 0, 0);
+  auto issue = [&](int st, int buf) {
+    // 32 tiles of 1 KiB: [key block 0: 8 K, 8 V][key block 1: 8 K, 8 V]; the second
+    // block of the last stage may lie past the tile's need but is inside the cache
+    for (int t = wave; t < 32; t += nw) {
+      int kb = min(st * 2 + (t >> 4), geom.key_blocks - 1);
+      const bf16_t *src = ((t & 8) ? Vc : Kc) + geom.off(tile.req, kvh, kb) + (size_t)(t & 7) * kTileElems + lane * 8;
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvStageBytes + t * 1024), 16, 0, 0);
     }
   };
   issue(0, 0);
-  for (int kb = 0; kb < n_kb; ++kb) {
-    const int buf = kb & 1;
-    __builtin_amdgcn_s_waitcnt(0x0070);  // my loads landed, my LDS reads of the previous block done
+  for (int st = 0; st < n_st; ++st) {
+    const int buf = st & 1;
+    __builtin_amdgcn_s_waitcnt(0x0070);  // my loads landed, my LDS reads of the previous stage done
     __syncthreads();
-    if (kb + 1 < n_kb) issue(kb + 1, buf ^ 1);
-    const char *base = lds + buf * kKvBlockBytes + lane * 16;
-
-    // scores S^T[key, query]
-    f32x16_t s[2];
+    if (st + 1 < n_st) issue(st + 1, buf ^ 1);
+    const int nblk = min(2, n_kb - st * 2);
+#pragma unroll 1
+    for (int j = 0; j < nblk; ++j) {
+      const int kb = st * 2 + j;
+      if (kb > qblk) break;  // this wave's rows end before the key block starts
+      const char *base = lds + buf * kKvStageBytes + j * 16384 + lane * 16;
+      f32x16_t s;
 #pragma unroll
-    for (int tq = 0; tq < 2; ++tq)
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[tq][r] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt) {
-      bf16x8_t kf = *(const bf16x8_t *)(base + dt * 1024);
-#pragma unroll
-      for (int tq = 0; tq < 2; ++tq) s[tq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[tq][dt], s[tq], 0, 0, 0);
-    }
-
-    bf16x8_t pf[2][2];
-#pragma unroll
-    for (int tq = 0; tq < 2; ++tq) {
+      for (int dt = 0; dt < 8; ++dt) {
+        bf16x8_t kf = *(const bf16x8_t *)(base + dt * 1024);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[dt], s, 0, 0, 0);
+      }
       float p[16];
-      const int qpos = (tile.qblk0 + tq) * 32 + tl;
       float mx = -INFINITY;
+      if (kb == qblk) {  // the diagonal block
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = s[tq][r];
-        if (kb >= tile.qblk0) {  // only the last two key blocks touch the diagonal
+        for (int r = 0; r < 16; ++r) {
           int kpos = kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          if (kpos > qpos) v = -INFINITY;
+          p[r] = kpos > qpos ? -INFINITY : s[r];
+          mx = fmaxf(mx, p[r]);
         }
-        p[r] = v;
-        mx = fmaxf(mx, v);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { p[r] = s[r]; mx = fmaxf(mx, p[r]); }
       }
       mx = xhalf_max(mx);
-      float m_new = fmaxf(m_run[tq], mx);  // finite from the first block on: key 0 is visible to every row
-      float rowsum = 0.f;
+      float m_new = fmaxf(m_run, mx);  // finite from the first block on: key 0 is visible to every row
+      float mc = m_new * c, rowsum = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        p[r] = exp2f((p[r] - m_new) * c);
+        p[r] = fast_exp2(p[r] * c - mc);
         rowsum += p[r];
       }
-      if (__any(m_new > m_run[tq])) {
-        float alpha = exp2f((m_run[tq] - m_new) * c);  // 0 on the first block
-        l_run[tq] *= alpha;
+      if (__any(m_new > m_run)) {
+        float alpha = fast_exp2((m_run - m_new) * c);  // 0 on the first block
+        l_run *= alpha;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) o[db][tq][r] *= alpha;
-        m_run[tq] = m_new;
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        m_run = m_new;
       }
-      l_run[tq] += rowsum;
-      pf[tq][0] = probs_operand(p, 0);
-      pf[tq][1] = probs_operand(p, 1);
-    }
-
-    // O^T[d, query] += V^T P^T
-#pragma unroll
-    for (int m = 0; m < 2; ++m)
+      l_run += rowsum;
+      bf16x8_t pf0 = probs_operand(p, 0), pf1 = probs_operand(p, 1);
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
-        bf16x8_t vf = *(const bf16x8_t *)(base + (8 + m * 4 + db) * 1024);
-#pragma unroll
-        for (int tq = 0; tq < 2; ++tq) o[db][tq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tq][m], o[db][tq], 0, 0, 0);
+        bf16x8_t v0 = *(const bf16x8_t *)(base + (8 + db) * 1024);
+        bf16x8_t v1 = *(const bf16x8_t *)(base + (12 + db) * 1024);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, pf0, o[db], 0, 0, 0);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, pf1, o[db], 0, 0, 0);
       }
+    }
   }
 
   // normalise and store into P(rows, qd): lane owns query tl, features 8g + 4hh + e of each d block
+  float inv = 1.0f / xhalf_sum(l_run);
 #pragma unroll
-  for (int tq = 0; tq < 2; ++tq) {
-    float inv = 1.0f / xhalf_sum(l_run[tq]);
-    int tb = rb0 + tq;
+  for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        int f0 = head * 128 + db * 32;
-        size_t off = ((size_t)tb * (qd >> 4) + ((f0 + 8 * g) >> 4)) * kTileElems + (((g & 1) << 5) + tl) * 8 + hh * 4;
-        *(bf16x4_t *)(out + off) = pack4(o[db][tq][4 * g] * inv, o[db][tq][4 * g + 1] * inv,
-                                         o[db][tq][4 * g + 2] * inv, o[db][tq][4 * g + 3] * inv);
-      }
-  }
+    for (int g = 0; g < 4; ++g) {
+      int f0 = head * 128 + db * 32;
+      size_t off = ((size_t)rb * (qd >> 4) + ((f0 + 8 * g) >> 4)) * kTileElems + (((g & 1) << 5) + tl) * 8 + hh * 4;
+      *(bf16x4_t *)(out + off) = pack4(o[db][4 * g] * inv, o[db][4 * g + 1] * inv, o[db][4 * g + 2] * inv,
+                                       o[db][4 * g + 3] * inv);
+    }
 }
 
 // ----------------------------------------------------------------------------
@@ -315,7 +308,7 @@ hipError_t mfma_attn_prefill(const bf16_t *q, const bf16_t *Kc, const bf16_t *Vc
                              int nq, int nkv, hipStream_t s) {
   if (n_tiles == 0) return hipSuccess;
   int G = nq / nkv;
-  k_attn_prefill<<<dim3(n_tiles, nkv), G * 64, 0, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq, G);
+  k_attn_prefill<<<dim3(n_tiles, nkv), 2 * G * 64, 0, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq, G);
   return hipGetLastError();
 }
 

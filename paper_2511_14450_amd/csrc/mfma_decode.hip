@@ -313,12 +313,16 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 
 hipError_t mfma_gemv_init() { return hipSuccess; }
 
-// K slices across workgroups: about 10 or more tiles per wave, and no more
-// workgroups than keep the chip busy a few times over
-int mfma_gemv_ksplit(int N, int K) {
+// K slices across workgroups: about 10 or more tiles per wave, no more
+// workgroups than keep the chip busy a few times over, and few enough slices
+// that the fp32 partial sums (written and read once per slice and token) stay
+// near a tenth of the weight bytes
+int mfma_gemv_ksplit(int N, int K, int batch) {
   int KT = K / 16, groups = N / kGroupRows;
+  int cap = (int)(0.025 * K / (batch > 0 ? batch : 1));
+  if (cap < 1) cap = 1;
   int best = 1;
-  for (int ks = 1; ks <= 64; ++ks) {
+  for (int ks = 1; ks <= 64 && ks <= cap; ++ks) {
     if (KT % (ks * NW) != 0) continue;
     if (KT / (ks * NW) < 10 || groups * ks > 2400) break;
     best = ks;

@@ -245,6 +245,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0x0070 | (((NST - 2) * LPW) & 15) | ((((NST - 2) * LPW) >> 4) << 14));
         __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_s_setprio(1);  // MFMA clusters win issue arbitration over the other wave's loads
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < FB; ++i)
@@ -259,6 +260,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
             if (((i * TB + j) & 1) == 1 && ((i * TB + j) >> 1) < LPW) issue1((i * TB + j) >> 1, lstep, buf);
           }
       } else {
+        __builtin_amdgcn_s_setprio(1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < FB; ++i)
@@ -273,6 +275,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
           }
       }
     }
+    __builtin_amdgcn_s_setprio(0);
     buf = nbuf;
   }
 #pragma unroll

@@ -131,14 +131,14 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.lens = take(sizeof(int) * c.max_batch);
     L.row_ext_dec = take(sizeof(int) * 32);
     L.qdec = take(es * (size_t)c.max_batch * c.n_kv_heads * 32 * 128);
-    L.ks_qkv = mfma_gemv_ksplit((int)(qd + 2 * kvd), (int)H);
-    L.ks_o = mfma_gemv_ksplit((int)H, (int)qd);
-    L.ks_gu = mfma_gemv_ksplit((int)(2 * I), (int)H);
-    L.ks_d = mfma_gemv_ksplit((int)H, (int)I);
+    L.ks_qkv = mfma_gemv_ksplit((int)(qd + 2 * kvd), (int)H, c.max_batch);
+    L.ks_o = mfma_gemv_ksplit((int)H, (int)qd, c.max_batch);
+    L.ks_gu = mfma_gemv_ksplit((int)(2 * I), (int)H, c.max_batch);
+    L.ks_d = mfma_gemv_ksplit((int)H, (int)I, c.max_batch);
     size_t pf = std::max(std::max((size_t)L.ks_qkv * (qd + 2 * kvd), (size_t)L.ks_o * H),
                          std::max((size_t)L.ks_gu * 2 * I, (size_t)L.ks_d * H));
     L.partial = take(sizeof(float) * pf * 32);
-    L.chunk_keys = mfma_decode_chunk_keys(c.max_seq);
+    L.chunk_keys = mfma_decode_chunk_keys(c.max_seq, c.max_batch * c.n_kv_heads);
     L.max_chunks = (c.max_seq + L.chunk_keys - 1) / L.chunk_keys;
     L.attn_part = take(sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks));
     L.counters = take(sizeof(unsigned) * (2 * I / 64 + (qd + 2 * kvd) / 64 + H / 64));

@@ -79,3 +79,8 @@ def test_c4_ragged_batch32_decode_at_long_context(phi3_layer):
     assert len(lens) == 32 and min(lens) >= 1024 and max(lens) <= 4096
     longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
     check_requests(phi3_layer, lens, 9300, sample_reqs=[longest, shortest], decode_steps=2)
+
+
+def test_c5_long_context_8192_sampled_rows_then_decode(phi3_layer):
+    # one long request (the 8192-token prompts of the long-sequence workload) next to a short one
+    check_requests(phi3_layer, [8192, 300], 9400, sample_reqs=[0, 1], decode_steps=2)

@@ -86,60 +86,65 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
     __builtin_amdgcn_s_waitcnt(0x0070);  // my loads landed, my LDS reads of the previous stage done
     __syncthreads();
     if (st + 1 < n_st) issue(st + 1, buf ^ 1);
-    const int nblk = min(2, n_kb - st * 2);
-#pragma unroll 1
-    for (int j = 0; j < nblk; ++j) {
-      const int kb = st * 2 + j;
-      if (kb > qblk) break;  // this wave's rows end before the key block starts
-      const char *base = lds + buf * kKvStageBytes + j * 16384 + lane * 16;
-      f32x16_t s;
+    const int kb0 = st * 2;
+    if (kb0 > qblk) continue;  // this wave's rows end before the stage's keys start (barrier is at the loop top)
+    const char *base = lds + buf * kKvStageBytes + lane * 16;
+    // scores of both 32-key blocks: two independent accumulator chains
+    f32x16_t s0, s1;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        bf16x8_t kf = *(const bf16x8_t *)(base + dt * 1024);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[dt], s, 0, 0, 0);
-      }
-      float p[16];
-      float mx = -INFINITY;
-      if (kb == qblk) {  // the diagonal block
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int kpos = kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-          p[r] = kpos > qpos ? -INFINITY : s[r];
-          mx = fmaxf(mx, p[r]);
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { p[r] = s[r]; mx = fmaxf(mx, p[r]); }
-      }
-      mx = xhalf_max(mx);
-      float m_new = fmaxf(m_run, mx);  // finite from the first block on: key 0 is visible to every row
-      float mc = m_new * c, rowsum = 0.f;
+    for (int dt = 0; dt < 8; ++dt) {
+      bf16x8_t k0 = *(const bf16x8_t *)(base + dt * 1024);
+      bf16x8_t k1 = *(const bf16x8_t *)(base + 16384 + dt * 1024);
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[dt], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[dt], s1, 0, 0, 0);
+    }
+    float p[32];
+    float mx = -INFINITY;
+    if (kb0 + 1 >= qblk) {  // the stage touches or passes the diagonal (a block past the
+                            // tile's need is fully masked here: its keys lie after every row)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        p[r] = fast_exp2(p[r] * c - mc);
-        rowsum += p[r];
+        int koff = 8 * (r >> 2) + 4 * hh + (r & 3);
+        p[r] = (kb0 * 32 + koff > qpos) ? -INFINITY : s0[r];
+        p[16 + r] = (kb0 * 32 + 32 + koff > qpos) ? -INFINITY : s1[r];
+        mx = fmaxf(mx, fmaxf(p[r], p[16 + r]));
       }
-      if (__any(m_new > m_run)) {
-        float alpha = fast_exp2((m_run - m_new) * c);  // 0 on the first block
-        l_run *= alpha;
+    } else {
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-        m_run = m_new;
-      }
-      l_run += rowsum;
-      bf16x8_t pf0 = probs_operand(p, 0), pf1 = probs_operand(p, 1);
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        bf16x8_t v0 = *(const bf16x8_t *)(base + (8 + db) * 1024);
-        bf16x8_t v1 = *(const bf16x8_t *)(base + (12 + db) * 1024);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, pf0, o[db], 0, 0, 0);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, pf1, o[db], 0, 0, 0);
+      for (int r = 0; r < 16; ++r) {
+        p[r] = s0[r];
+        p[16 + r] = s1[r];
+        mx = fmaxf(mx, fmaxf(p[r], p[16 + r]));
       }
     }
+    mx = xhalf_max(mx);
+    float m_new = fmaxf(m_run, mx);  // finite from the first stage on: key 0 is visible to every row
+    float mc = m_new * c, rowsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+      p[r] = fast_exp2(p[r] * c - mc);
+      rowsum += p[r];
+    }
+    if (__any(m_new > m_run)) {
+      float alpha = fast_exp2((m_run - m_new) * c);  // 0 on the first stage
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      m_run = m_new;
+    }
+    l_run += rowsum;
+    bf16x8_t pf[4] = {probs_operand(p, 0), probs_operand(p, 1), probs_operand(p + 16, 0), probs_operand(p + 16, 1)};
+#pragma unroll
+    for (int h2 = 0; h2 < 4; ++h2)   // (key block, MFMA step) pairs
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        bf16x8_t vf = *(const bf16x8_t *)(base + (h2 >> 1) * 16384 + (8 + (h2 & 1) * 4 + db) * 1024);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[h2], o[db], 0, 0, 0);
+      }
   }
 
   // normalise and store into P(rows, qd): lane owns query tl, features 8g + 4hh + e of each d block

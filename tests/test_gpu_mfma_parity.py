@@ -130,3 +130,38 @@ def test_decode_graph_replays_equal_kernel_by_kernel_launches():
         xd = to_dev(synth.hidden_states(2, shape, 720), "bf16")
         assert torch.equal(a.decode_step(xd), b.decode_step(xd))
     a.destroy(); b.destroy()
+
+
+def test_mfma_batch_32_and_single_token_prompts():
+    # 32 resident requests (the widest decode block), among them 1-token prompts
+    lens = [1, 2, 31, 32, 33, 63, 64, 65] + [5] * 24
+    _, gst = run_mfma(SHAPE_G2, 1, lens, 3, 730, check_kv=False)
+    gst.destroy()
+
+
+def test_mfma_decode_fills_the_cache_to_capacity():
+    """70 decode steps from a 58-token prompt: crosses two 32-key block boundaries and a
+    decode chunk boundary and ends exactly at max_seq; one more step must be refused."""
+    import paper_2511_14450_amd as hyp
+    from paper_2511_14450_amd import binding
+    ost, gst = run_mfma(SHAPE_G2, 1, [58, 3], 70, 731, check_kv=True)
+    assert gst.context_len(0) == 128
+    with pytest.raises(hyp.HypError) as e:
+        gst.decode_step(to_dev(synth.hidden_states(2, SHAPE_G2, 999), "bf16"))
+    assert e.value.status == binding.HYP_ECAPACITY
+    gst.destroy()
+
+
+def test_mfma_three_layer_stage_composition():
+    # stage [0,3) == stage [0,1) then stage [1,3): the residual stream crosses stages as bf16
+    shape = SHAPE_G2
+    layers = [synth.layer_weights(shape, l, 732, sigma=0.05) for l in range(3)]
+    lens = [90, 41]
+    x = synth.hidden_states(sum(lens), shape, 733)
+    ost = orc.Stage(shape, layers, 2, 140, "f32")
+    ref = ost.prefill(x, lens)
+    a = make_gpu_stage(shape, layers[:1], 2, 140, 131)
+    b = make_gpu_stage(shape, layers[1:], 2, 140, 131, l_start=1)
+    got = to_host(b.prefill(a.prefill(to_dev(x, "bf16"), lens), lens))
+    check(got, ref, x, "bf16", "chained stages")
+    a.destroy(); b.destroy()

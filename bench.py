@@ -241,10 +241,18 @@ def main():
         "roofline": {k: dominant[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic")},
         "kernels": rows,
     }
+    # what this device delivers at best, measured in the same run: the MFMA pipes from
+    # registers (Gaussian operands make the chip clock down; constants do not) and a
+    # plain streaming read
+    stage.destroy()
+    del stage, x, y
+    torch.cuda.empty_cache()
+    out["measured_ceilings"] = {
+        "mfma_bf16_gaussian_operands_tflops": hyp.hyp_measure_mfma_ceiling(True),
+        "mfma_bf16_constant_operands_tflops": hyp.hyp_measure_mfma_ceiling(False),
+        "hbm_stream_read_gbs": hyp.hyp_measure_hbm_read_ceiling(4),
+    }
     if not args.no_cpu_baseline:
-        stage.destroy()
-        del stage
-        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
 

@@ -192,6 +192,21 @@ HYP_API hyp_status_t stage_profile(hyp_stage_t *stage, uint32_t class_mask);
 HYP_API hyp_status_t stage_profile_read(hyp_stage_t *stage, int32_t kernel_class, double *total_ms,
                                 int64_t *launches);
 
+/* Measurement aids: ceilings of the device measured in place, to set beside the
+ * datasheet peaks in a roofline.  Neither needs a stage; both time three launches
+ * with HIP events on `hip_stream` and wait for them.
+ *   hyp_measure_mfma_ceiling     bf16 MFMA rate (TFLOP/s) of a register-only loop of
+ *       v_mfma_f32_32x32x16_bf16 on every SIMD; operands N(0,1) (gaussian != 0) or the
+ *       constant 1.0.  scratch: device, 16-byte aligned, >= 2.2 MB, overwritten.
+ *   hyp_measure_hbm_read_ceiling rate (GB/s) of a plain streaming read of `buffer`
+ *       (device, 16-byte aligned, >= 1 GiB - well beyond the 256 MB memory-side cache;
+ *       its last 16 bytes may be overwritten).
+ * Errors: HYP_EINVAL (null / too small / misaligned), HYP_EDEVICE. */
+HYP_API hyp_status_t hyp_measure_mfma_ceiling(void *scratch, size_t scratch_bytes, int32_t gaussian,
+                                      void *hip_stream, double *tflops_out);
+HYP_API hyp_status_t hyp_measure_hbm_read_ceiling(const void *buffer, size_t bytes, void *hip_stream,
+                                          double *gbs_out);
+
 /* 1 if the MFMA kernels run for this stage, 0 if the shape-generic kernels do
  * (fp32 stages, head_dim != 128, widths that are not multiples of 256, or
  * HYP_FLAG_PLAIN_KERNELS). */

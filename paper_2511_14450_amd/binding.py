@@ -22,7 +22,8 @@ HYP_FLAG_NO_GRAPH = 2
 
 EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_decode_step",
            "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",
-           "stage_uses_mfma", "stage_profile", "stage_profile_read")
+           "stage_uses_mfma", "stage_profile", "stage_profile_read",
+           "hyp_measure_mfma_ceiling", "hyp_measure_hbm_read_ceiling")
 
 KERNEL_CLASSES = ("add_norm", "gemm_qkv", "attn_prefill", "gemm_o", "gemm_gateup", "gemm_down", "gemv_qkv",
                   "dec_qkv_finish", "attn_decode", "gemv_o", "gemv_gateup", "dec_swiglu", "gemv_down")
@@ -94,6 +95,10 @@ def load_library() -> C.CDLL:
     lib.stage_profile.argtypes = [C.c_void_p, C.c_uint32]
     lib.stage_profile_read.restype = C.c_int
     lib.stage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.hyp_measure_mfma_ceiling.restype = C.c_int
+    lib.hyp_measure_mfma_ceiling.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
+    lib.hyp_measure_hbm_read_ceiling.restype = C.c_int
+    lib.hyp_measure_hbm_read_ceiling.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
     lib.stage_uses_mfma.restype = C.c_int32
     lib.stage_uses_mfma.argtypes = [C.c_void_p]
     _LIB = lib
@@ -252,6 +257,28 @@ def stage_profile_read(stage: Stage, kernel_class: str):
     _check(load_library().stage_profile_read(stage.handle, KERNEL_CLASSES.index(kernel_class), C.byref(ms), C.byref(n)),
            stage.handle)
     return ms.value, n.value
+
+
+def hyp_measure_mfma_ceiling(gaussian: bool = True) -> float:
+    """bf16 MFMA TFLOP/s of a register-only loop on the current device."""
+    scratch = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
+    out = C.c_double()
+    st = load_library().hyp_measure_mfma_ceiling(scratch.data_ptr(), scratch.numel(), 1 if gaussian else 0,
+                                                 C.c_void_p(torch.cuda.current_stream().cuda_stream), C.byref(out))
+    if st != HYP_OK:
+        raise HypError(st, "hyp_measure_mfma_ceiling failed")
+    return out.value
+
+
+def hyp_measure_hbm_read_ceiling(gib: int = 4) -> float:
+    """GB/s of a plain streaming read of a `gib` GiB buffer on the current device."""
+    buf = torch.empty(gib << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    out = C.c_double()
+    st = load_library().hyp_measure_hbm_read_ceiling(buf.data_ptr(), buf.numel(),
+                                                     C.c_void_p(torch.cuda.current_stream().cuda_stream), C.byref(out))
+    if st != HYP_OK:
+        raise HypError(st, "hyp_measure_hbm_read_ceiling failed")
+    return out.value
 
 
 def stage_uses_mfma(stage: Stage) -> bool:

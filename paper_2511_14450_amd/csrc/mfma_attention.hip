@@ -322,13 +322,12 @@ size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks) {
 }
 
 hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom,
-                            const int *lens, float *part, unsigned *counters, bf16_t *out, int nq, int nkv,
-                            int batch, int max_chunks, int chunk_keys, hipStream_t s) {
+                            const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
+                            int max_chunks, int chunk_keys, hipStream_t s) {
   int G = nq / nkv;
   k_attn_decode<<<dim3(max_chunks, nkv, batch), 64, 0, s>>>(qdec, Kc, Vc, geom, lens, part, nq, G, max_chunks, chunk_keys);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  (void)counters;
   k_attn_decode_merge<<<dim3(nq, batch), 128, 0, s>>>(part, lens, out, nq, max_chunks, chunk_keys);
   return hipGetLastError();
 }

@@ -311,8 +311,6 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 
 }  // namespace
 
-hipError_t mfma_gemv_init() { return hipSuccess; }
-
 // K slices across workgroups: about 10 or more tiles per wave, no more
 // workgroups than keep the chip busy a few times over, and few enough slices
 // that the fp32 partial sums (written and read once per slice and token) stay

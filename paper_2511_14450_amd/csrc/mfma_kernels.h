@@ -20,13 +20,11 @@ struct QkvEpilogue {
 hipError_t mfma_pack_weight(const bf16_t *src0, const bf16_t *src1, const bf16_t *src2, int rows0,
                             int rows1, bf16_t *dst, int N, int K, int mode, int I, hipStream_t s);
 
-hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *delta_bf,
-                         const float *delta_part, int n_part, size_t part_stride, const bf16_t *gain,
+hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *delta_bf, const bf16_t *gain,
                          bf16_t *y, bf16_t *hidden_out, const int *row_ext, int rows, int H, float eps,
                          bool final_mode, hipStream_t s);
 
 hipError_t mfma_gemm_init();
-hipError_t mfma_gemv_init();
 // out^T[N, rows] = W[N,K] X[rows,K]^T with the epilogue `epi`; rows % 32 == 0,
 // N % 256 == 0, K % 32 == 0, K >= 128
 hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
@@ -76,8 +74,8 @@ hipError_t mfma_dec_begin(const bf16_t *hidden_in, float *xres, const bf16_t *ga
 
 // split-KV decode attention + fixed-order merge; out row b of P(32, nq*128)
 hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom,
-                            const int *lens, float *part, unsigned *counters, bf16_t *out, int nq, int nkv,
-                            int batch, int max_chunks, int chunk_keys, hipStream_t s);
+                            const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
+                            int max_chunks, int chunk_keys, hipStream_t s);
 size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks);
 // keys per decode-attention chunk (one wave each): 128, or 256 when that still leaves
 // too few waves to matter (measured: 8 x 10 heads x 2K context runs 11 % faster with

@@ -49,21 +49,19 @@ __global__ void __launch_bounds__(256) k_pack_weight(const bf16_t *__restrict__ 
 
 // ----------------------------------------------------------------------------
 // Residual add + RMS Norm over internal rows.
-//   x = (first ? hidden_in[row_ext] : xres) + sum_s delta_s          (fp32)
+//   x = (first ? hidden_in[row_ext] : xres) + delta                  (fp32)
 //   xres = x;  y = x * rsqrt(mean(x^2) + eps) * g   -> P(rows, H)   (norm mode)
 //   hidden_out[row_ext] = x                                           (final mode)
-// delta is either one fragment-order bf16 matrix P(rows, H) (prefill GEMM
-// output) or n_part fp32 partial sums [n_part][32][H] (decode split-K output).
-// A 256-thread block owns RPW consecutive rows (8 for prefill, 1 for the few rows
-// of a decode step so that more workgroups share the latency-bound sums);
+// delta is the fragment-order bf16 output P(rows, H) of the preceding GEMM.
+// A 256-thread block owns RPW consecutive rows (8, or 1 when there are only a few
+// rows so that more workgroups share the work);
 // thread t works on row t % RPW.
 // ----------------------------------------------------------------------------
 template <int MODE, int RPW>  // MODE 0: norm -> y ; 1: final -> hidden_out
 __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hidden_in,
                                                   float *__restrict__ xres,
                                                   const bf16_t *__restrict__ delta_bf,
-                                                  const float *__restrict__ delta_part, int n_part,
-                                                  size_t part_stride, const bf16_t *__restrict__ gain,
+                                                  const bf16_t *__restrict__ gain,
                                                   bf16_t *__restrict__ y, bf16_t *__restrict__ hidden_out,
                                                   const int *__restrict__ row_ext, int H, float eps) {
   constexpr int CPR = 256 / RPW;  // threads per row
@@ -89,11 +87,6 @@ __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hid
       if (delta_bf) {
         u16x8_t d = *(const u16x8_t *)(delta_bf + frag_offset(row, c * 8, H));
         for (int e = 0; e < 8; ++e) v[e] += bf16_to_f32(d.v[e]);
-      }
-      for (int s = 0; s < n_part; ++s) {
-        const float *p = delta_part + s * part_stride + (size_t)row * H + c * 8;
-        f32x4_t a = *(const f32x4_t *)p, b = *(const f32x4_t *)(p + 4);
-        for (int e = 0; e < 4; ++e) { v[e] += a[e]; v[4 + e] += b[e]; }
       }
     }
     if (MODE == 0) {
@@ -387,13 +380,12 @@ hipError_t mfma_pack_weight(const bf16_t *src0, const bf16_t *src1, const bf16_t
   return hipGetLastError();
 }
 
-hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *delta_bf,
-                         const float *delta_part, int n_part, size_t part_stride, const bf16_t *gain,
+hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *delta_bf, const bf16_t *gain,
                          bf16_t *y, bf16_t *hidden_out, const int *row_ext, int rows, int H, float eps,
                          bool final_mode, hipStream_t s) {
   if (rows == 0) return hipSuccess;
 #define HYP_ADD_NORM(MODE, RPW) \
-  k_add_norm<MODE, RPW><<<rows / RPW, 256, 0, s>>>(hidden_in, xres, delta_bf, delta_part, n_part, part_stride, gain, y, hidden_out, row_ext, H, eps)
+  k_add_norm<MODE, RPW><<<rows / RPW, 256, 0, s>>>(hidden_in, xres, delta_bf, gain, y, hidden_out, row_ext, H, eps)
   if (rows <= 64) {
     if (final_mode) HYP_ADD_NORM(1, 1); else HYP_ADD_NORM(0, 1);
   } else {

@@ -35,7 +35,7 @@ struct Layout {
   size_t tok_req = 0, tok_pos = 0, lens = 0, iota = 0;
   // MFMA path only
   size_t q = 0, delta = 0, row_ext = 0, row_pos = 0, row_req = 0, tiles = 0, req_len = 0, row_ext_dec = 0, qdec = 0,
-         partial = 0, attn_part = 0, counters = 0, attn_counters = 0, ssq = 0;
+         partial = 0, attn_part = 0, counters = 0, ssq = 0;
   size_t kv_bytes = 0;  // bytes of each of Kc, Vc over all layers
   int rows_cap = 0;     // internal rows the scratch holds
   int key_blocks = 0;   // 32-key blocks per (request, kv head)
@@ -142,7 +142,6 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.max_chunks = (c.max_seq + L.chunk_keys - 1) / L.chunk_keys;
     L.attn_part = take(sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks));
     L.counters = take(sizeof(unsigned) * (2 * I / 64 + (qd + 2 * kvd) / 64 + H / 64));
-    L.attn_counters = take(sizeof(unsigned) * (size_t)c.max_batch * c.n_kv_heads);
     L.ssq = take(sizeof(float) * 32 * (H / 64));
     L.total = off;
     return;
@@ -322,7 +321,7 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
   bf16_t *m = at<bf16_t>(st, L.m), *delta = at<bf16_t>(st, L.delta);
   const int *row_ext = at<int>(st, L.row_ext);
   CacheGeom geom = cache_geom(st);
-  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, nullptr, 0, 0, at<bf16_t>(st, L.layers[0].g1), y,
+  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, at<bf16_t>(st, L.layers[0].g1), y,
                             nullptr, row_ext, rows, d.H, d.eps, false, s));
   for (int l = 0; l < st->n_layers; ++l) {
     const LayerPtrs &p = L.layers[l];
@@ -336,15 +335,15 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
     PROF(st, HYP_K_ATTN_PREFILL, mfma_attn_prefill(q, e.Kc, e.Vc, geom, attn, at<PrefillTile>(st, L.tiles), n_tiles,
                                   at<int>(st, L.req_len), d.nq, d.nkv, s));
     PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_STORE, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, delta, d.H, nullptr, s));
-    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, p.g2), y, nullptr, row_ext, rows, d.H,
+    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, at<bf16_t>(st, p.g2), y, nullptr, row_ext, rows, d.H,
                               d.eps, false, s));
     PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, nullptr, s));
     PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, nullptr, s));
     if (l + 1 < st->n_layers)
-      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, at<bf16_t>(st, L.layers[l + 1].g1), y, nullptr,
+      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, at<bf16_t>(st, L.layers[l + 1].g1), y, nullptr,
                                 row_ext, rows, d.H, d.eps, false, s));
     else
-      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, 0, 0, nullptr, nullptr, (bf16_t *)hidden_out, row_ext, rows,
+      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, nullptr, (bf16_t *)hidden_out, row_ext, rows,
                                 d.H, d.eps, true, s));
   }
   return HYP_OK;
@@ -380,7 +379,7 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const void *hidden_i
     a.qdec = at<bf16_t>(st, L.qdec); a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
     PROF(st, HYP_K_GEMV_QKV, mfma_dec_gemv(DEC_QKV, a, s));
     PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(a.qdec, Kc, Vc, geom, a.lens, at<float>(st, L.attn_part),
-                                                 at<unsigned>(st, L.attn_counters), attn, d.nq, d.nkv, st->batch,
+                                                 attn, d.nq, d.nkv, st->batch,
                                                  L.max_chunks, L.chunk_keys, s));
     DecGemv o = base;
     o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.ksplit = L.ks_o;
@@ -552,7 +551,6 @@ hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_
 
   if (st->mfma) {
     hipError_t e = mfma_gemm_init();
-    if (e == hipSuccess) e = mfma_gemv_init();
     if (e != hipSuccess) { st->err = std::string("kernel attributes: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
     rc = pack_weights_mfma(st, layers);
   } else {

@@ -186,6 +186,7 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
   const int kb_begin = k0 >> 5;
   const int kb_end = min((k0 + chunk_keys) >> 5, (nkeys + 31) >> 5);
   const float c = kLog2e * 0.08838834764831845f;
+  const int key_limit = nkeys;
 
   bf16x8_t qf[8];
   const bf16_t *qb = qdec + ((size_t)req * geom.nkv + kvh) * (32 * 128);
@@ -216,28 +217,38 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
     for (int dt = 0; dt < 8; ++dt) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[dt], qf[dt], s, 0, 0, 0);
     float p[16];
     float mx = -INFINITY;
+    if ((kb + 1) * 32 > key_limit) {  // only the last block of a chunk can hold keys past the end
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      int kpos = kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-      float v = kpos < nkeys ? s[r] : -INFINITY;
-      p[r] = v;
-      mx = fmaxf(mx, v);
+      for (int r = 0; r < 16; ++r) {
+        int kpos = kb * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+        p[r] = kpos < key_limit ? s[r] : -INFINITY;
+        mx = fmaxf(mx, p[r]);
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        p[r] = s[r];
+        mx = fmaxf(mx, p[r]);
+      }
     }
     mx = xhalf_max(mx);
-    float m_new = fmaxf(m_run, mx);  // finite: the first key of a chunk is always valid
-    float alpha = exp2f((m_run - m_new) * c);
-    float rowsum = 0.f;
+    float m_new = fmaxf(m_run, mx);  // finite: the first key of a chunk is always valid and comes first
+    float mc = m_new * c, rowsum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      p[r] = exp2f((p[r] - m_new) * c);
+      p[r] = fast_exp2(p[r] * c - mc);
       rowsum += p[r];
     }
-    l_run = l_run * alpha + rowsum;
-    m_run = m_new;
+    if (__any(m_new > m_run)) {  // the accumulators are rescaled only when some maximum moved
+      float alpha = fast_exp2((m_run - m_new) * c);  // 0 on the first block
+      l_run *= alpha;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+      for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      m_run = m_new;
+    }
+    l_run += rowsum;
     bf16x8_t pf0 = probs_operand(p, 0), pf1 = probs_operand(p, 1);
 #pragma unroll
     for (int db = 0; db < 4; ++db) {

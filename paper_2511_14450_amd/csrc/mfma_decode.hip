@@ -159,26 +159,46 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
     }
     __syncthreads();
     if (!is_last) return;
+  }
+  // The finishing workgroup.  Its loads are issued together so that their round trips
+  // overlap: first the sums of squares behind the RMS Norm factor (16 row groups per
+  // thread at once), then the partial sums.
+  float ssq_v[16];
+  const int ssq_tkn = threadIdx.x & 31, ssq_part_id = threadIdx.x >> 5;
+  if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      int g = ssq_part_id + 8 * u;
+      ssq_v[u] = g < p.n_ssq ? p.ssq_in[g * 32 + ssq_tkn] : 0.f;
+    }
+  }
+  if (p.ksplit > 1) {
     // Plain loads are enough here: every 256-byte run of `partial` has exactly one
     // writer in this launch, this XCD's L2 was invalidated when the launch began,
     // and nothing in this launch read these lines before, so a line is either
     // absent (fetched from memory, where the writer's store has completed) or was
-    // put there by a writer on this very XCD.  All slices are loaded before any is
-    // added, so the round trips overlap.
-    for (int idx = threadIdx.x; idx < n_pairs; idx += NW * 64) {
-      int f = idx % kGroupRows, token = idx / kGroupRows;
-      const float *src = p.partial + (size_t)token * p.N + fb0 * 32 + f;
-      float sum = 0.f;
-      int s = 0;
-      for (; s + 8 <= p.ksplit; s += 8) {
-        float v[8];
+    // put there by a writer on this very XCD.  Two (token, row) pairs per thread and
+    // eight slices of each are in flight at once; slices beyond ksplit are masked
+    // rather than peeled, so the gather costs ceil(ksplit / 8) round trips.
+    for (int idx0 = threadIdx.x; idx0 < n_pairs; idx0 += 2 * NW * 64) {
+      const int idx1 = idx0 + NW * 64;
+      const bool has1 = idx1 < n_pairs;
+      const float *src0 = p.partial + (size_t)(idx0 / kGroupRows) * p.N + fb0 * 32 + idx0 % kGroupRows;
+      const float *src1 = p.partial + (size_t)((has1 ? idx1 : idx0) / kGroupRows) * p.N + fb0 * 32 + (has1 ? idx1 : idx0) % kGroupRows;
+      float sum0 = 0.f, sum1 = 0.f;
+      for (int s = 0; s < p.ksplit; s += 8) {
+        float v0[8], v1[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(s + u) * 32 * p.N];
+        for (int u = 0; u < 8; ++u) {
+          const bool in = s + u < p.ksplit;
+          v0[u] = in ? src0[(size_t)(s + u) * 32 * p.N] : 0.f;
+          v1[u] = in && has1 ? src1[(size_t)(s + u) * 32 * p.N] : 0.f;
+        }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) sum += v[u];
+        for (int u = 0; u < 8; ++u) { sum0 += v0[u]; sum1 += v1[u]; }
       }
-      for (; s < p.ksplit; ++s) sum += src[(size_t)s * 32 * p.N];
-      fin[token][f] = sum;
+      fin[idx0 / kGroupRows][idx0 % kGroupRows] = sum0;
+      if (has1) fin[idx1 / kGroupRows][idx1 % kGroupRows] = sum1;
     }
   }
   if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {
@@ -186,10 +206,11 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
     // fixed order (8 interleaved partial sums, then those in order)
     __shared__ float ssq_part[8][32];
     {
-      int tkn = threadIdx.x & 31, part = threadIdx.x >> 5;
       float ss = 0.f;
-      for (int g = part; g < p.n_ssq; g += 8) ss += p.ssq_in[g * 32 + tkn];
-      ssq_part[part][tkn] = ss;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) ss += ssq_v[u];
+      for (int g = ssq_part_id + 8 * 16; g < p.n_ssq; g += 8) ss += p.ssq_in[g * 32 + ssq_tkn];
+      ssq_part[ssq_part_id][ssq_tkn] = ss;
     }
     __syncthreads();
     if (threadIdx.x < 32) {

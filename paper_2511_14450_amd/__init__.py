@@ -12,3 +12,11 @@ from .binding import (  # noqa: F401
     stage_workspace_bytes, KERNEL_CLASSES, stage_config, hyp_measure_mfma_ceiling,
     hyp_measure_hbm_read_ceiling,
 )
+
+
+def __getattr__(name):
+    # the chain module is also a program (python -m paper_2511_14450_amd.chain): load it on demand
+    if name == "StageChain":
+        from .chain import StageChain
+        return StageChain
+    raise AttributeError(name)

@@ -24,6 +24,7 @@ EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_deco
            "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",
            "stage_uses_mfma", "stage_profile", "stage_profile_read",
            "hyp_measure_mfma_ceiling", "hyp_measure_hbm_read_ceiling")
+EXPORTS_PLAN = ("hypsplit_dp", "hypsched_rt", "hypsched_simulate")  # include/hyp_plan.h
 
 KERNEL_CLASSES = ("add_norm", "gemm_qkv", "attn_prefill", "gemm_o", "gemm_gateup", "gemm_down", "gemv_qkv",
                   "dec_qkv_finish", "attn_decode", "gemv_o", "gemv_gateup", "dec_swiglu", "gemv_down")
@@ -101,6 +102,13 @@ def load_library() -> C.CDLL:
     lib.hyp_measure_hbm_read_ceiling.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
     lib.stage_uses_mfma.restype = C.c_int32
     lib.stage_uses_mfma.argtypes = [C.c_void_p]
+    dp, ip, bp = C.POINTER(C.c_double), C.POINTER(C.c_int32), C.POINTER(C.c_uint8)
+    lib.hypsplit_dp.restype = C.c_int
+    lib.hypsplit_dp.argtypes = [C.c_int32, C.c_int32, dp, dp, dp, dp, C.c_double, ip, dp, ip]
+    lib.hypsched_rt.restype = C.c_int
+    lib.hypsched_rt.argtypes = [C.c_int32, dp, dp, bp, dp, dp, C.c_double, C.c_double, ip]
+    lib.hypsched_simulate.restype = C.c_int
+    lib.hypsched_simulate.argtypes = [C.c_int32, dp, C.c_int32, dp, dp, ip, dp, dp, bp, dp, ip, dp]
     _LIB = lib
     return lib
 
@@ -292,3 +300,60 @@ def stage_destroy(stage: Stage) -> None:
         stage.handle = None
         if status != HYP_OK:
             raise HypError(status, "stage_destroy failed")
+
+
+# ---------------------------------------------------------------- include/hyp_plan.h
+def _dbl(v):
+    return (C.c_double * len(v))(*[float(x) for x in v])
+
+
+def hypsplit_dp(f: Sequence[float], m: Sequence[float], Cj: Sequence[float], Mj: Sequence[float], eps: float):
+    """(p* as a list p_1..p_{T-1}, or None if no partition fits the memory limits; tau*)."""
+    N, T = len(f), len(Cj)
+    if len(m) != N or len(Mj) != T:
+        raise ValueError("f / m need one entry per block, C / M one per tier")
+    p = (C.c_int32 * max(T - 1, 1))()
+    tau, ok = C.c_double(), C.c_int32()
+    st = load_library().hypsplit_dp(N, T, _dbl(f), _dbl(m), _dbl(Cj), _dbl(Mj), float(eps), p, C.byref(tau), C.byref(ok))
+    if st != HYP_OK:
+        raise HypError(st, "hypsplit_dp rejected its arguments")
+    return ([int(p[i]) for i in range(T - 1)] if ok.value else None), tau.value
+
+
+def hypsched_rt(F_new: float, m_act: float, Ck: Sequence[float], M_avail: Sequence[float], available: Sequence[bool],
+                F_run_rem: Sequence[float], F_wait: Sequence[float]) -> Optional[int]:
+    """Index of the node Algorithm 2 picks, or None if no node is eligible."""
+    K = len(Ck)
+    if not (len(M_avail) == len(available) == len(F_run_rem) == len(F_wait) == K):
+        raise ValueError("one entry per node in every array")
+    k = C.c_int32()
+    av = (C.c_uint8 * max(K, 1))(*[1 if a else 0 for a in available])
+    st = load_library().hypsched_rt(K, _dbl(Ck), _dbl(M_avail), av, _dbl(F_run_rem), _dbl(F_wait),
+                                    float(F_new), float(m_act), C.byref(k))
+    if st != HYP_OK:
+        raise HypError(st, "hypsched_rt rejected its arguments")
+    return None if k.value < 0 else int(k.value)
+
+
+def hypsched_simulate(arrivals: Sequence[float], F: Sequence[float], m_act: Sequence[float],
+                      Cjk: Sequence[Sequence[float]], Mjk: Sequence[Sequence[float]], transfer: Sequence[float],
+                      available: Optional[Sequence[Sequence[bool]]] = None):
+    """(node[task][tier], finish[task][tier]) of the FIFO queue model driven by HypSched-RT."""
+    T, n = len(F), len(arrivals)
+    if len(m_act) != T or len(Cjk) != T or len(Mjk) != T or len(transfer) != max(T - 1, 0):
+        raise ValueError("per-tier arrays need one entry per tier, transfer one per boundary")
+    per = (C.c_int32 * T)(*[len(c) for c in Cjk])
+    flatC = [x for c in Cjk for x in c]
+    flatM = [x for c in Mjk for x in c]
+    av = None
+    if available is not None:
+        flat = [1 if a else 0 for c in available for a in c]
+        av = (C.c_uint8 * len(flat))(*flat)
+    node = (C.c_int32 * (n * T))()
+    fin = (C.c_double * (n * T))()
+    st = load_library().hypsched_simulate(n, _dbl(arrivals), T, _dbl(F), _dbl(m_act), per, _dbl(flatC), _dbl(flatM),
+                                          av, _dbl(transfer) if T > 1 else None, node, fin)
+    if st != HYP_OK:
+        raise HypError(st, "hypsched_simulate rejected its arguments")
+    return ([[int(node[q * T + j]) for j in range(T)] for q in range(n)],
+            [[float(fin[q * T + j]) for j in range(T)] for q in range(n)])

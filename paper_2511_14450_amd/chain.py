@@ -199,16 +199,77 @@ def run_whole_model(model: str, split: Sequence[int], prompt: int, generate: int
     return res
 
 
+def measure_block_costs(model: str, prompt: int, generate: int, batch: int = 1, seed: int = 251114450):
+    """What Algorithm 1 needs to know about a block, measured on this device: f = the
+    seconds one block spends on a request of the given shape (prefill + every decode
+    step; all blocks of a model have one shape, so one block is measured), m = the bytes
+    a block adds to a stage (repacked weights + its share of the KV cache)."""
+    m = MODELS[model]
+    shape = _Shape(m)
+    chain = StageChain(shape, [0, 1], _synthetic_layer(shape, seed), batch, prompt + generate + 1, batch * prompt)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed + 6)
+    x = torch.randn((batch * prompt, m["hidden"]), generator=gen, device="cuda").to(torch.bfloat16)
+    xd = torch.randn((batch, m["hidden"]), generator=gen, device="cuda").to(torch.bfloat16)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    seconds = 0.0
+    for rep in range(2):  # the first pass warms up (graph capture)
+        e0.record()
+        chain.prefill(x, [prompt] * batch)
+        for _ in range(generate - 1):
+            chain.decode_step(xd)
+        e1.record()
+        torch.cuda.synchronize()
+        seconds = e0.elapsed_time(e1) * 1e-3
+    cfg = binding.stage_config(shape, batch, prompt + generate + 1, batch * prompt)
+    bytes_per_block = binding.stage_workspace_bytes(cfg, 0, 2) - binding.stage_workspace_bytes(cfg, 0, 1)
+    chain.destroy()
+    return seconds, float(bytes_per_block)
+
+
+def plan_split(model: str, tiers: Sequence[Sequence[float]], prompt: int, generate: int, eps: float, batch: int = 1):
+    """HypSplit-DP (Sec. IV-A) on measured block costs.  tiers = [(capacity, memory GB), ...]
+    in the order the pipeline visits them; capacities are relative (Table I lists TOPS):
+    the largest stands for this device, f_i / C_j is then the time of block i on tier j."""
+    n = MODELS[model]["blocks"]
+    f1, m1 = measure_block_costs(model, prompt, generate, batch)
+    cap_ref = max(float(c) for c, _ in tiers)
+    C = [float(c) / cap_ref for c, _ in tiers]
+    M = [float(g) * 1e9 for _, g in tiers]
+    t0 = time.perf_counter()
+    p, tau = binding.hypsplit_dp([f1] * n, [m1] * n, C, M, eps)
+    dt = time.perf_counter() - t0
+    plan = {"model": model, "blocks": n, "tiers": [[float(c), float(g)] for c, g in tiers], "eps": eps,
+            "f_seconds_per_block": f1, "m_bytes_per_block": m1, "p": p, "tau_seconds": tau,
+            "hypsplit_dp_seconds": dt}
+    if p is not None:
+        b = [0] + p + [n]
+        plan["blocks_per_tier"] = [b[j + 1] - b[j] for j in range(len(tiers))]
+        plan["tier_load_seconds"] = [f1 * (b[j + 1] - b[j]) / C[j] for j in range(len(tiers))]
+    return plan
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--model", choices=sorted(MODELS), default="phi3_medium")
     ap.add_argument("--split", default=None, help="blocks per stage, e.g. 20,13,7 (default: four equal stages)")
+    ap.add_argument("--tiers", default=None,
+                    help="plan the split with HypSplit-DP instead: capacity:memoryGB per tier, e.g. 67:8,157:16,200:32")
+    ap.add_argument("--eps", type=float, default=1e-3, help="precision of the binary search (Sec. V-A uses 1e-3)")
     ap.add_argument("--prompt", type=int, default=64)
     ap.add_argument("--generate", type=int, default=128)
     ap.add_argument("--batch", type=int, default=1)
     a = ap.parse_args()
     n = MODELS[a.model]["blocks"]
-    split = [int(v) for v in a.split.split(",")] if a.split else [n // 4] * 4
+    if a.tiers:
+        tiers = [tuple(float(v) for v in t.split(":")) for t in a.tiers.split(",")]
+        plan = plan_split(a.model, tiers, a.prompt, a.generate, a.eps, a.batch)
+        print(json.dumps(plan))
+        if plan["p"] is None:
+            raise SystemExit("no partition fits the tiers' memory")
+        split = plan["blocks_per_tier"]
+    else:
+        split = [int(v) for v in a.split.split(",")] if a.split else [n // 4] * 4
     print(json.dumps(run_whole_model(a.model, split, a.prompt, a.generate, a.batch)))
 
 

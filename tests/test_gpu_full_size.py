@@ -27,7 +27,7 @@ def sample_rows(L, rng, n_random=6):
     return rows
 
 
-def check_requests(layer, lens, seed, sample_reqs, decode_steps):
+def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE):
     B, T = len(lens), sum(lens)
     cap = max(lens) + decode_steps
     x = synth.hidden_states(T, SHAPE, seed)
@@ -84,3 +84,10 @@ def test_c4_ragged_batch32_decode_at_long_context(phi3_layer):
 def test_c5_long_context_8192_sampled_rows_then_decode(phi3_layer):
     # one long request (the 8192-token prompts of the long-sequence workload) next to a short one
     check_requests(phi3_layer, [8192, 300], 9400, sample_reqs=[0, 1], decode_steps=2)
+
+
+def test_llama3_8b_shaped_block_sampled_rows_then_decode():
+    # the second model of Table I: hidden 4096, 32 query / 8 KV heads, FFN 14336
+    shape = synth.LLAMA3_8B
+    layer = synth.layer_weights(shape, 0, synth.WORKLOADS["n4_llama3_stage8"].seed)
+    check_requests(layer, [2048, 777, 64], 9500, sample_reqs=[0, 1, 2], decode_steps=2, SHAPE=shape)

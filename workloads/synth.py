@@ -77,6 +77,9 @@ class BlockShape:
 TINY = BlockShape(256, 4, 2, 64, 1024, dtype="f32")
 TINY_BF16 = dataclasses.replace(TINY, dtype="bf16")
 PHI3_MEDIUM = BlockShape(5120, 40, 10, 128, 17920, dtype="bf16")
+# the paper's second model (Table I: 32 blocks, hidden 4096, GQA); head counts and FFN width are
+# the architecture's published ones, the paper does not list them
+LLAMA3_8B = BlockShape(4096, 32, 8, 128, 14336, dtype="bf16")
 
 
 @dataclasses.dataclass(frozen=True)
@@ -110,6 +113,7 @@ WORKLOADS = {
     "c3_stage10": Workload("c3_stage10", 2, PHI3_MEDIUM, 10, (2048,) * 8, 128),
     "c4_decode_heavy": Workload("c4_decode_heavy", 3, PHI3_MEDIUM, 10, (0,) * 32, 256, (1024, 4096)),
     "c5_long": Workload("c5_long", 4, PHI3_MEDIUM, 20, (8192,) * 8, 1024),
+    "n4_llama3_stage8": Workload("n4_llama3_stage8", 5, LLAMA3_8B, 8, (2048,) * 8, 128),
 }
 
 

@@ -6,29 +6,45 @@
 namespace hyp {
 
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATEUP = 2 };
-enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_QKV = 2 };
+enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_QKV = 2, EPI_RESID = 3 };
 
-struct QkvEpilogue {
-  bf16_t *Kc, *Vc;  // caches of the layer
-  CacheGeom geom;
-  int qd, kvd;
-  const float *cos_tab, *sin_tab;  // [position][64]
-  const int *row_pos, *row_req;    // per internal row
+// What the epilogue of a prefill GEMM needs besides its output; fields an epilogue does
+// not use stay null.
+struct GemmEpilogue {
+  // EPI_QKV
+  bf16_t *Kc = nullptr, *Vc = nullptr;  // caches of the layer
+  CacheGeom geom = {};
+  int qd = 0, kvd = 0;
+  const float *cos_tab = nullptr, *sin_tab = nullptr;  // [position][64]
+  const int *row_pos = nullptr, *row_req = nullptr;    // per internal row
+  // EPI_QKV, EPI_SWIGLU: RMS Norm factor of every input row (the rows carry the gain only)
+  const float *rstd = nullptr;
+  // EPI_RESID: residual stream A(T', N), gains of the following norm, padding map,
+  // sums of squares out [N / 64][T']
+  float *xres = nullptr;
+  const bf16_t *gain = nullptr;
+  const int *row_ext = nullptr;
+  float *ssq_part = nullptr;
 };
 
 // dst = P(N, K) of the row-permuted concatenation [src0; src1; src2]
 hipError_t mfma_pack_weight(const bf16_t *src0, const bf16_t *src1, const bf16_t *src2, int rows0,
                             int rows1, bf16_t *dst, int N, int K, int mode, int I, hipStream_t s);
 
-hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *delta_bf, const bf16_t *gain,
-                         bf16_t *y, bf16_t *hidden_out, const int *row_ext, int rows, int H, float eps,
-                         bool final_mode, hipStream_t s);
+// first block's input: x = hidden_in (external rows) -> residual A(T', H), y' = x * gain -> P(T', H), rstd
+hipError_t mfma_prefill_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y, float *rstd,
+                              const int *row_ext, int rows, int H, float eps, hipStream_t s);
+// stage output: hidden_out (external rows) = residual + delta
+hipError_t mfma_prefill_end(const float *xres, const bf16_t *delta_bf, bf16_t *hidden_out, const int *row_ext,
+                            int rows, int H, hipStream_t s);
+// rstd[row] from the per-group sums of squares of EPI_RESID
+hipError_t mfma_rstd(const float *ssq_part, float *rstd, int rows, int H, float eps, hipStream_t s);
 
 hipError_t mfma_gemm_init();
 // out^T[N, rows] = W[N,K] X[rows,K]^T with the epilogue `epi`; rows % 32 == 0,
 // N % 256 == 0, K % 32 == 0, K >= 128
 hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
-                     int out_K, const QkvEpilogue *qkv, hipStream_t s);
+                     int out_K, const GemmEpilogue &ep, hipStream_t s);
 
 // Causal GQA attention over the prompt (flash-style, scores never stored).
 //   q P(rows, nq*128) ; caches of the layer ; out P(rows, nq*128)

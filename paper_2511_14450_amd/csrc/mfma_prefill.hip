@@ -48,21 +48,22 @@ __global__ void __launch_bounds__(256) k_pack_weight(const bf16_t *__restrict__ 
 }
 
 // ----------------------------------------------------------------------------
-// Residual add + RMS Norm over internal rows.
-//   x = (first ? hidden_in[row_ext] : xres) + delta                  (fp32)
-//   xres = x;  y = x * rsqrt(mean(x^2) + eps) * g   -> P(rows, H)   (norm mode)
-//   hidden_out[row_ext] = x                                           (final mode)
-// delta is the fragment-order bf16 output P(rows, H) of the preceding GEMM.
+// The two ends of a prefill over internal rows (everything between them happens in
+// GEMM epilogues).
+//   MODE 0  x = hidden_in[row_ext] ; residual = x (accumulator order) ;
+//           y' = x * g -> P(rows, H) ; rstd = rsqrt(mean(x^2) + eps)
+//           (the norm factor is applied by the consuming GEMM's epilogue)
+//   MODE 1  hidden_out[row_ext] = residual + delta, delta = P(rows, H) bf16 of the last GEMM
 // A 256-thread block owns RPW consecutive rows (8, or 1 when there are only a few
-// rows so that more workgroups share the work);
-// thread t works on row t % RPW.
+// rows so that more workgroups share the work); thread t works on row t % RPW.
 // ----------------------------------------------------------------------------
-template <int MODE, int RPW>  // MODE 0: norm -> y ; 1: final -> hidden_out
+template <int MODE, int RPW>  // MODE 0: first block's input ; 1: stage output
 __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hidden_in,
                                                   float *__restrict__ xres,
                                                   const bf16_t *__restrict__ delta_bf,
                                                   const bf16_t *__restrict__ gain,
-                                                  bf16_t *__restrict__ y, bf16_t *__restrict__ hidden_out,
+                                                  bf16_t *__restrict__ y, float *__restrict__ rstd,
+                                                  bf16_t *__restrict__ hidden_out,
                                                   const int *__restrict__ row_ext, int H, float eps) {
   constexpr int CPR = 256 / RPW;  // threads per row
   __shared__ float red[RPW][CPR + 1];
@@ -71,30 +72,30 @@ __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hid
   int ext = row_ext[row];
   int nchunk = H >> 3;
   float ss = 0.f;
-  float *xr = xres + (size_t)row * H;
   for (int c = cg; c < nchunk; c += CPR) {
     float v[8];
+    float *xa = xres + acc_offset(row, c * 8, H), *xb = xres + acc_offset(row, c * 8 + 4, H);
     if (ext < 0) {
       for (int e = 0; e < 8; ++e) v[e] = 0.f;
+    } else if (MODE == 0) {
+      u16x8_t h = *(const u16x8_t *)(hidden_in + (size_t)ext * H + c * 8);
+      for (int e = 0; e < 8; ++e) v[e] = bf16_to_f32(h.v[e]);
     } else {
-      if (hidden_in) {
-        u16x8_t h = *(const u16x8_t *)(hidden_in + (size_t)ext * H + c * 8);
-        for (int e = 0; e < 8; ++e) v[e] = bf16_to_f32(h.v[e]);
-      } else {
-        f32x4_t a = *(const f32x4_t *)(xr + c * 8), b = *(const f32x4_t *)(xr + c * 8 + 4);
-        for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
-      }
-      if (delta_bf) {
-        u16x8_t d = *(const u16x8_t *)(delta_bf + frag_offset(row, c * 8, H));
-        for (int e = 0; e < 8; ++e) v[e] += bf16_to_f32(d.v[e]);
-      }
+      f32x4_t a = *(const f32x4_t *)xa, b = *(const f32x4_t *)xb;
+      u16x8_t d = *(const u16x8_t *)(delta_bf + frag_offset(row, c * 8, H));
+      for (int e = 0; e < 4; ++e) { v[e] = a[e] + bf16_to_f32(d.v[e]); v[4 + e] = b[e] + bf16_to_f32(d.v[4 + e]); }
     }
     if (MODE == 0) {
       f32x4_t a, b;
       for (int e = 0; e < 4; ++e) { a[e] = v[e]; b[e] = v[4 + e]; }
-      *(f32x4_t *)(xr + c * 8) = a;
-      *(f32x4_t *)(xr + c * 8 + 4) = b;
-      for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+      *(f32x4_t *)xa = a;
+      *(f32x4_t *)xb = b;
+      u16x8_t gg = *(const u16x8_t *)(gain + c * 8), o;
+      for (int e = 0; e < 8; ++e) {
+        ss += v[e] * v[e];
+        o.v[e] = f2bf_dev(v[e] * bf16_to_f32(gg.v[e]));
+      }
+      *(u16x8_t *)(y + frag_offset(row, c * 8, H)) = o;
     } else if (ext >= 0) {
       u16x8_t o;
       for (int e = 0; e < 8; ++e) o.v[e] = f2bf_dev(v[e]);
@@ -104,19 +105,22 @@ __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hid
   if (MODE == 1) return;
   red[r8][cg] = ss;
   __syncthreads();
-  float tot = 0.f;
-  for (int i = 0; i < CPR; ++i) tot += red[r8][i];
-  float rs = 1.0f / sqrtf(tot / (float)H + eps);
-  for (int c = cg; c < nchunk; c += CPR) {
-    f32x4_t a = *(const f32x4_t *)(xr + c * 8), b = *(const f32x4_t *)(xr + c * 8 + 4);
-    u16x8_t gg = *(const u16x8_t *)(gain + c * 8);
-    u16x8_t o;
-    for (int e = 0; e < 4; ++e) {
-      o.v[e] = f2bf_dev(a[e] * rs * bf16_to_f32(gg.v[e]));
-      o.v[4 + e] = f2bf_dev(b[e] * rs * bf16_to_f32(gg.v[4 + e]));
-    }
-    *(u16x8_t *)(y + frag_offset(row, c * 8, H)) = o;
+  if (cg == 0) {
+    float tot = 0.f;
+    for (int i = 0; i < CPR; ++i) tot += red[r8][i];
+    rstd[row] = 1.0f / sqrtf(tot / (float)H + eps);
   }
+}
+
+// rstd[row] = 1 / sqrt(mean square + eps) from the sums of squares the residual
+// epilogue left per 64-feature group: ssq_part[group][row], added in group order.
+__global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part, float *__restrict__ rstd, int rows,
+                                              int groups, float inv_H, float eps) {
+  int row = blockIdx.x * 256 + threadIdx.x;
+  if (row >= rows) return;
+  float tot = 0.f;
+  for (int g = 0; g < groups; ++g) tot += ssq_part[(size_t)g * rows + row];
+  rstd[row] = 1.0f / sqrtf(tot * inv_H + eps);
 }
 
 // ----------------------------------------------------------------------------
@@ -147,13 +151,19 @@ struct GemmParams {
   int gm;            // token tiles per band
   int n_tiles;
   // epilogue
-  bf16_t *out;       // EPI_STORE: P(T', N); EPI_SWIGLU: P(T', N/2); EPI_QKV: q as P(T', qd)
+  bf16_t *out;       // EPI_STORE: P(T', N); EPI_SWIGLU: P(T', N/2); EPI_QKV: q as P(T', qd); EPI_RESID: y' as P(T', N)
   int out_K;         // row length of `out`
   bf16_t *Kc, *Vc;   // EPI_QKV: caches of this layer
   CacheGeom geom;
   int qd, kvd;
   const float *cos_tab, *sin_tab;  // [pos][64]
   const int *row_pos, *row_req;    // per internal row
+  const float *rstd;               // EPI_QKV / EPI_SWIGLU: RMS Norm factor of every row of X
+  // EPI_RESID: residual stream A(T', N), gains of the next norm, padding map, statistics out
+  float *xres;
+  const bf16_t *gain;
+  const int *row_ext;
+  float *ssq_part;                 // [N / 64][T']
 };
 
 __device__ __forceinline__ void store_block(bf16_t *out, int out_K, int tb, int f0, int lane,
@@ -304,13 +314,48 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     for (int j = 0; j < TB; ++j) {
       int tb = tb0 + wt * TB + j;
       if (tb >= p.tok_blocks) continue;
+      const float rs = p.rstd[tb * 32 + tl];  // the input rows carry gain only: W (x g r) = r W (x g)
       float v[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float g = acc[0][j][r], u = acc[1][j][r];
+        float g = acc[0][j][r] * rs, u = acc[1][j][r] * rs;
         v[r] = g / (1.0f + __expf(-g)) * u;
       }
       store_block(p.out, p.out_K, tb, (tile_n * 4 + wf) * 32, lane, v);
+    }
+  } else if (EPI == EPI_RESID) {
+    // x += W a ; y' = x * gain of the next norm ; sum of squares of these 64 features per token.
+    // Padding rows stay zero.
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      int tb = tb0 + wt * TB + j;
+      if (tb >= p.tok_blocks) continue;
+      const int row = tb * 32 + tl;
+      const bool live = p.row_ext[row] >= 0;
+      float ss = 0.f;
+#pragma unroll
+      for (int i = 0; i < FB; ++i) {
+        const int fb = nb0 + wf * FB + i;
+        float *xb = p.xres + ((size_t)tb * p.feat_blocks + fb) * 1024 + lane * 4;
+        float v[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4_t old = *(const f32x4_t *)(xb + g * 256);
+          bf16x4_t gg = *(const bf16x4_t *)(p.gain + fb * 32 + 8 * g + 4 * hh);
+          f32x4_t nw;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float xn = live ? old[e] + acc[i][j][4 * g + e] : 0.f;
+            nw[e] = xn;
+            ss += xn * xn;
+            v[4 * g + e] = xn * bf16_to_f32(gg.v[e]);
+          }
+          *(f32x4_t *)(xb + g * 256) = nw;
+        }
+        store_block(p.out, p.out_K, tb, fb * 32, lane, v);
+      }
+      ss += __shfl_xor(ss, 32, 64);
+      if (hh == 0) p.ssq_part[(size_t)((nb0 + wf * FB) >> 1) * (p.tok_blocks * 32) + row] = ss;
     }
   } else {  // EPI_QKV
     const int n0 = tile_n * 256;              // first packed row of this tile
@@ -321,6 +366,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
       if (tb >= p.tok_blocks) continue;
       int row = tb * 32 + tl;
       int pos = p.row_pos[row], req = p.row_req[row];
+      const float rs = p.rstd[row];
       if (n0 < p.qd + p.kvd) {
         // q or k: rotate the pair (d, d + 64) by the angle of this position
         float lo[16], hi[16];
@@ -330,7 +376,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
           f32x4_t s4 = *(const f32x4_t *)(p.sin_tab + (size_t)pos * 64 + ib + 8 * g + 4 * hh);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            float a = acc[0][j][4 * g + e], b = acc[1][j][4 * g + e];
+            float a = acc[0][j][4 * g + e] * rs, b = acc[1][j][4 * g + e] * rs;
             lo[4 * g + e] = a * c4[e] - b * s4[e];
             hi[4 * g + e] = b * c4[e] + a * s4[e];
           }
@@ -361,7 +407,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             int d = ib + i * 64 + 8 * (r >> 2) + 4 * hh + (r & 3);
-            vb[(size_t)(m * 4 + (d >> 5)) * kTileElems + (khh * 32 + (d & 31)) * 8 + e] = f2bf_dev(acc[i][j][r]);
+            vb[(size_t)(m * 4 + (d >> 5)) * kTileElems + (khh * 32 + (d & 31)) * 8 + e] = f2bf_dev(acc[i][j][r] * rs);
           }
       }
     }
@@ -380,18 +426,26 @@ hipError_t mfma_pack_weight(const bf16_t *src0, const bf16_t *src1, const bf16_t
   return hipGetLastError();
 }
 
-hipError_t mfma_add_norm(const bf16_t *hidden_in, float *xres, const bf16_t *delta_bf, const bf16_t *gain,
-                         bf16_t *y, bf16_t *hidden_out, const int *row_ext, int rows, int H, float eps,
-                         bool final_mode, hipStream_t s) {
+hipError_t mfma_prefill_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y, float *rstd,
+                              const int *row_ext, int rows, int H, float eps, hipStream_t s) {
   if (rows == 0) return hipSuccess;
-#define HYP_ADD_NORM(MODE, RPW) \
-  k_add_norm<MODE, RPW><<<rows / RPW, 256, 0, s>>>(hidden_in, xres, delta_bf, gain, y, hidden_out, row_ext, H, eps)
-  if (rows <= 64) {
-    if (final_mode) HYP_ADD_NORM(1, 1); else HYP_ADD_NORM(0, 1);
-  } else {
-    if (final_mode) HYP_ADD_NORM(1, 8); else HYP_ADD_NORM(0, 8);
-  }
-#undef HYP_ADD_NORM
+  if (rows <= 64) k_add_norm<0, 1><<<rows, 256, 0, s>>>(hidden_in, xres, nullptr, gain, y, rstd, nullptr, row_ext, H, eps);
+  else k_add_norm<0, 8><<<rows / 8, 256, 0, s>>>(hidden_in, xres, nullptr, gain, y, rstd, nullptr, row_ext, H, eps);
+  return hipGetLastError();
+}
+
+hipError_t mfma_prefill_end(const float *xres, const bf16_t *delta_bf, bf16_t *hidden_out, const int *row_ext,
+                            int rows, int H, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  float *x = const_cast<float *>(xres);
+  if (rows <= 64) k_add_norm<1, 1><<<rows, 256, 0, s>>>(nullptr, x, delta_bf, nullptr, nullptr, nullptr, hidden_out, row_ext, H, 0.f);
+  else k_add_norm<1, 8><<<rows / 8, 256, 0, s>>>(nullptr, x, delta_bf, nullptr, nullptr, nullptr, hidden_out, row_ext, H, 0.f);
+  return hipGetLastError();
+}
+
+hipError_t mfma_rstd(const float *ssq_part, float *rstd, int rows, int H, float eps, hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  k_rstd<<<(rows + 255) / 256, 256, 0, s>>>(ssq_part, rstd, rows, H / 64, 1.0f / (float)H, eps);
   return hipGetLastError();
 }
 
@@ -399,11 +453,12 @@ hipError_t mfma_gemm_init() {
   hipError_t e = hipFuncSetAttribute((const void *)k_gemm<EPI_STORE>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_QKV>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
   return e;
 }
 
 hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
-                     int out_K, const QkvEpilogue *qkv, hipStream_t s) {
+                     int out_K, const GemmEpilogue &ep, hipStream_t s) {
   if (rows == 0) return hipSuccess;
   GemmParams p = {};
   p.X = X; p.W = W; p.KT = K / 16; p.tok_blocks = rows / 32; p.feat_blocks = N / 32;
@@ -411,13 +466,13 @@ hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N,
   p.gm = tiles_t < 8 ? tiles_t : 8;
   p.n_tiles = tiles_t * tiles_n;
   p.out = out; p.out_K = out_K;
-  if (qkv) {
-    p.Kc = qkv->Kc; p.Vc = qkv->Vc; p.geom = qkv->geom; p.qd = qkv->qd; p.kvd = qkv->kvd;
-    p.cos_tab = qkv->cos_tab; p.sin_tab = qkv->sin_tab; p.row_pos = qkv->row_pos; p.row_req = qkv->row_req;
-  }
+  p.Kc = ep.Kc; p.Vc = ep.Vc; p.geom = ep.geom; p.qd = ep.qd; p.kvd = ep.kvd;
+  p.cos_tab = ep.cos_tab; p.sin_tab = ep.sin_tab; p.row_pos = ep.row_pos; p.row_req = ep.row_req;
+  p.rstd = ep.rstd; p.xres = ep.xres; p.gain = ep.gain; p.row_ext = ep.row_ext; p.ssq_part = ep.ssq_part;
   int grid = (p.n_tiles + 7) / 8 * 8;
   if (epi == EPI_STORE) k_gemm<EPI_STORE><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
   else if (epi == EPI_SWIGLU) k_gemm<EPI_SWIGLU><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
+  else if (epi == EPI_RESID) k_gemm<EPI_RESID><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
   else k_gemm<EPI_QKV><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
   return hipGetLastError();
 }

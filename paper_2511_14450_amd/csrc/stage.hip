@@ -35,7 +35,7 @@ struct Layout {
   size_t tok_req = 0, tok_pos = 0, lens = 0, iota = 0;
   // MFMA path only
   size_t q = 0, delta = 0, row_ext = 0, row_pos = 0, row_req = 0, tiles = 0, req_len = 0, row_ext_dec = 0, qdec = 0,
-         partial = 0, attn_part = 0, counters = 0, ssq = 0;
+         partial = 0, attn_part = 0, counters = 0, ssq = 0, rstd = 0, ssq_part = 0;
   size_t kv_bytes = 0;  // bytes of each of Kc, Vc over all layers
   int rows_cap = 0;     // internal rows the scratch holds
   int key_blocks = 0;   // 32-key blocks per (request, kv head)
@@ -123,6 +123,8 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.attn = take(es * R * qd);
     L.m = take(es * R * I);
     L.delta = take(es * R * H);
+    L.rstd = take(sizeof(float) * R);
+    L.ssq_part = take(sizeof(float) * R * (H / 64));
     L.row_ext = take(sizeof(int) * R);
     L.row_pos = take(sizeof(int) * R);
     L.row_req = take(sizeof(int) * R);
@@ -321,30 +323,39 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
   bf16_t *m = at<bf16_t>(st, L.m), *delta = at<bf16_t>(st, L.delta);
   const int *row_ext = at<int>(st, L.row_ext);
   CacheGeom geom = cache_geom(st);
-  PROF(st, HYP_K_ADD_NORM, mfma_add_norm((const bf16_t *)hidden_in, xres, nullptr, at<bf16_t>(st, L.layers[0].g1), y,
-                            nullptr, row_ext, rows, d.H, d.eps, false, s));
+  float *rstd = at<float>(st, L.rstd), *ssq_part = at<float>(st, L.ssq_part);
+  PROF(st, HYP_K_ADD_NORM, mfma_prefill_begin((const bf16_t *)hidden_in, xres, at<bf16_t>(st, L.layers[0].g1), y, rstd,
+                                               row_ext, rows, d.H, d.eps, s));
   for (int l = 0; l < st->n_layers; ++l) {
     const LayerPtrs &p = L.layers[l];
-    QkvEpilogue e;
+    const bool last = l + 1 == st->n_layers;
+    GemmEpilogue e;
     e.Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l);
     e.Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
     e.geom = geom; e.qd = d.qd; e.kvd = d.kvd;
     e.cos_tab = at<float>(st, L.cos_tab); e.sin_tab = at<float>(st, L.sin_tab);
     e.row_pos = at<int>(st, L.row_pos); e.row_req = at<int>(st, L.row_req);
-    PROF(st, HYP_K_GEMM_QKV, mfma_gemm(EPI_QKV, y, at<bf16_t>(st, p.wqkv), rows, d.qd + 2 * d.kvd, d.H, q, d.qd, &e, s));
+    e.rstd = rstd;
+    PROF(st, HYP_K_GEMM_QKV, mfma_gemm(EPI_QKV, y, at<bf16_t>(st, p.wqkv), rows, d.qd + 2 * d.kvd, d.H, q, d.qd, e, s));
     PROF(st, HYP_K_ATTN_PREFILL, mfma_attn_prefill(q, e.Kc, e.Vc, geom, attn, at<PrefillTile>(st, L.tiles), n_tiles,
                                   at<int>(st, L.req_len), d.nq, d.nkv, s));
-    PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_STORE, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, delta, d.H, nullptr, s));
-    PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, at<bf16_t>(st, p.g2), y, nullptr, row_ext, rows, d.H,
-                              d.eps, false, s));
-    PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, nullptr, s));
-    PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, nullptr, s));
-    if (l + 1 < st->n_layers)
-      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, at<bf16_t>(st, L.layers[l + 1].g1), y, nullptr,
-                                row_ext, rows, d.H, d.eps, false, s));
-    else
-      PROF(st, HYP_K_ADD_NORM, mfma_add_norm(nullptr, xres, delta, nullptr, nullptr, (bf16_t *)hidden_out, row_ext, rows,
-                                d.H, d.eps, true, s));
+    // residual add, the next norm's gain and its statistics all happen in the epilogue
+    GemmEpilogue r;
+    r.xres = xres; r.row_ext = row_ext; r.ssq_part = ssq_part;
+    r.gain = at<bf16_t>(st, p.g2);
+    PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_RESID, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, y, d.H, r, s));
+    PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, rows, d.H, d.eps, s));
+    GemmEpilogue g;
+    g.rstd = rstd;
+    PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, g, s));
+    if (!last) {
+      r.gain = at<bf16_t>(st, L.layers[l + 1].g1);
+      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_RESID, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, y, d.H, r, s));
+      PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, rows, d.H, d.eps, s));
+    } else {
+      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, GemmEpilogue(), s));
+      PROF(st, HYP_K_ADD_NORM, mfma_prefill_end(xres, delta, (bf16_t *)hidden_out, row_ext, rows, d.H, s));
+    }
   }
   return HYP_OK;
 }

@@ -32,7 +32,9 @@ namespace {
 //              squares of this row group -> ssq_out   (RMS Norm of the next
 //              sub-layer, applied by that sub-layer's epilogue as a scale:
 //              W (x * rstd * g) = rstd * W (x * g))
-//   DEC_FINAL  x += sum ; hidden_out = x
+//   DEC_FINAL  x += sum ; hidden_out = x ; the finisher of row group 0 also counts the
+//              step's token into the cached lengths (every reader of them in this
+//              step ran in an earlier kernel)
 // ----------------------------------------------------------------------------
 constexpr int FBW = 2, NW = 4, UNROLL = 10;
 constexpr int kGroupRows = FBW * 32;
@@ -58,6 +60,7 @@ struct DecGemvParams {
   float *ssq_out;
   bf16_t *hidden_out;
   int H;
+  int *lens_advance;  // DEC_FINAL: cached lengths to bump once the step's last kernel finishes
 };
 
 template <int EPI>
@@ -273,6 +276,7 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
         p.hidden_out[(size_t)b * p.H + n0 + f] = f2bf_dev(xn);
       }
     }
+    if (EPI == DEC_FINAL && blockIdx.x == 0 && p.lens_advance && threadIdx.x < p.batch) p.lens_advance[threadIdx.x] += 1;
     if (EPI == DEC_RESID) {
       __syncthreads();
       if (threadIdx.x < p.batch) {
@@ -356,7 +360,7 @@ hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s) {
   p.ssq_in = a.ssq_in; p.n_ssq = a.n_ssq; p.inv_H = a.n_ssq ? 1.0f / (float)(a.n_ssq * kGroupRows) : 0.f; p.eps = a.eps;
   p.lens = a.lens; p.cos_tab = a.cos_tab; p.sin_tab = a.sin_tab; p.qdec = a.qdec; p.Kc = a.Kc; p.Vc = a.Vc;
   p.geom = a.geom; p.nq = a.nq; p.nkv = a.nkv; p.m_out = a.m_out; p.I = a.I; p.xres = a.xres; p.gain = a.gain;
-  p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H;
+  p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H; p.lens_advance = a.lens_advance;
   dim3 grid(a.N / kGroupRows, a.ksplit);
   switch (epi) {
     case DEC_QKV: k_dec_gemv<DEC_QKV><<<grid, NW * 64, 0, s>>>(p); break;

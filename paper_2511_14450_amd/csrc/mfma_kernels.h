@@ -81,6 +81,7 @@ struct DecGemv {
   float *ssq_out = nullptr;
   bf16_t *hidden_out = nullptr;
   int H = 0;
+  int *lens_advance = nullptr;  // DEC_FINAL: lengths to increment at the end of the step
 };
 hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s);
 int mfma_gemv_ksplit(int N, int K, int batch);

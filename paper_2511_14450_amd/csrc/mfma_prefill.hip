@@ -119,7 +119,13 @@ __global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part
   int row = blockIdx.x * 256 + threadIdx.x;
   if (row >= rows) return;
   float tot = 0.f;
-  for (int g = 0; g < groups; ++g) tot += ssq_part[(size_t)g * rows + row];
+  for (int g0 = 0; g0 < groups; g0 += 16) {  // 16 loads in flight, added in group order
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = g0 + u < groups ? ssq_part[(size_t)(g0 + u) * rows + row] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) tot += v[u];
+  }
   rstd[row] = 1.0f / sqrtf(tot * inv_H + eps);
 }
 

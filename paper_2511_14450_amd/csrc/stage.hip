@@ -407,6 +407,7 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const void *hidden_i
       PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_RESID, w, s));
     } else {
       w.hidden_out = (bf16_t *)hidden_out;
+      w.lens_advance = at<int>(st, L.lens);
       PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_FINAL, w, s));
     }
   }
@@ -681,7 +682,7 @@ hyp_status_t stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hid
                     : st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, st->batch, iota, lens)
                                : run_plain<float>(st, hidden_in, hidden_out, st->batch, iota, lens);
   if (rc != HYP_OK) return rc;
-  HIP_TRY(st, advance_lens(at<int>(st, st->L.lens), st->batch, st->stream));
+  if (!st->mfma) HIP_TRY(st, advance_lens(at<int>(st, st->L.lens), st->batch, st->stream));  // the MFMA path's last kernel does it
   for (int b = 0; b < st->batch; ++b) st->lens[b] += 1;
   return HYP_OK;
 }

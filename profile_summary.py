@@ -4,6 +4,7 @@
   kernel stats :  python profile_summary.py stats  <dir>/<name>_kernel_stats.csv
   HBM traffic  :  python profile_summary.py traffic <fetch>_counter_collection.csv <write>_counter_collection.csv
                   [--json profiles/traffic_c3_stage10.json --workload c3_stage10]
+  MFMA / waits :  python profile_summary.py counters <dir>/<name>_counter_collection.csv
 
 FETCH_SIZE / WRITE_SIZE are reported by rocprofv3 in KiB per dispatch; both are scaled by
 what the same counter reads for the 256 MiB device copy that `bench.py --traffic-calibration`
@@ -20,6 +21,9 @@ import sys
 
 CLASS_OF = [  # (regex on the kernel name, grid-x test, class)
     (r"k_gemm<2>", "gemm_qkv"), (r"k_gemm<1>", "gemm_gateup"), (r"k_attn_prefill", "attn_prefill"),
+    # in the one-block counter run the O projection is the only residual-epilogue GEMM and the
+    # down projection (last block of the stage) the only plain-epilogue one
+    (r"k_gemm<3>", "gemm_o"), (r"k_gemm<0>", "gemm_down"), (r"k_rstd", "add_norm"),
     (r"k_attn_decode_merge", "attn_decode_merge"), (r"k_attn_decode", "attn_decode"),
     (r"k_dec_gemv<0>", "gemv_qkv"), (r"k_dec_gemv<1>", "gemv_gateup"), (r"k_add_norm", "add_norm"),
     (r"k_dec_begin", "dec_begin"),
@@ -27,11 +31,10 @@ CLASS_OF = [  # (regex on the kernel name, grid-x test, class)
 
 
 # kernels shared by two classes, told apart by their launch size on the c3 workload
-# (total work-items): prefill O / down projections differ only in K, so both have the
-# grid of a [16384 x 5120] output and are reported together; decode O / down differ in ksplit
+# (total work-items): the decode O / down projections differ in ksplit
 NAME_BY_GRID = {
     "k_dec_gemv<2>/grid163840": "gemv_o", "k_dec_gemv<3>/grid573440": "gemv_down",
-    "k_dec_gemv<2>/grid573440": "gemv_down", "k_gemm<0>/grid655360": "gemm_o+gemm_down",
+    "k_dec_gemv<2>/grid573440": "gemv_down",
 }
 
 
@@ -48,7 +51,7 @@ def classify(row) -> str:
     for pat, cls in CLASS_OF:
         if re.search(pat, n):
             return cls
-    if n.startswith("k_gemm<0>") or n.startswith("k_dec_gemv<2>") or n.startswith("k_dec_gemv<3>"):
+    if n.startswith("k_dec_gemv<2>") or n.startswith("k_dec_gemv<3>"):
         return n + f"/grid{grid}"
     return n
 
@@ -104,14 +107,34 @@ def traffic(fetch_csv, write_csv, out_json, workload):
                    "hbm_bytes_per_launch": result}, open(out_json, "w"), indent=1)
 
 
+def counters(path):
+    """MFMA busy / wait / LDS conflict ratios per kernel from one --pmc run with
+    SQ_VALU_MFMA_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE GRBM_GUI_ACTIVE."""
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(path)):
+        agg[short(r["Kernel_Name"]) + " grid " + r["Grid_Size"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    print(f"{'kernel':34s} {'cycles/XCD':>11s} {'MFMA busy':>10s} {'wave wait':>10s} {'LDS conflict':>12s}")
+    for k, v in agg.items():
+        if not re.match(r"k_(gemm|attn|dec_gemv|mfma_only|add_norm|rstd)", k):
+            continue
+        a = {c: sum(x) / len(x) for c, x in v.items()}
+        cyc = a["GRBM_GUI_ACTIVE"] / 8
+        busy = a["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024 / cyc
+        wait = a["SQ_WAIT_ANY"] / a["SQ_WAVE_CYCLES"]
+        conf = a["SQ_LDS_BANK_CONFLICT"] / a["SQ_LDS_IDX_ACTIVE"] if a["SQ_LDS_IDX_ACTIVE"] else 0.0
+        print(f"{k:34s} {cyc:11.0f} {busy:10.3f} {wait:10.3f} {conf:12.3f}")
+
+
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
-    ap.add_argument("mode", choices=["stats", "traffic"])
+    ap.add_argument("mode", choices=["stats", "traffic", "counters"])
     ap.add_argument("files", nargs="+")
     ap.add_argument("--json")
     ap.add_argument("--workload", default="c3_stage10")
     a = ap.parse_args()
     if a.mode == "stats":
         stats(a.files[0])
+    elif a.mode == "counters":
+        counters(a.files[0])
     else:
         traffic(a.files[0], a.files[1], a.json, a.workload)

@@ -102,10 +102,17 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
   for (; t + UNROLL <= p.tiles_per_wave; t += UNROLL) {
     bf16x8_t xf[UNROLL], wf[FBW][UNROLL];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
+    for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
       for (int i = 0; i < FBW; ++i) wf[i][u] = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)(t + u) * kTileElems));
-      xf[u] = *(const bf16x8_t *)(xp + (size_t)(t + u) * kTileElems);
+    // token columns beyond the batch feed output columns nobody reads: their lanes skip the load
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xf[u][e] = 0;
+    if ((lane & 31) < p.batch) {
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) xf[u] = *(const bf16x8_t *)(xp + (size_t)(t + u) * kTileElems);
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)

@@ -36,7 +36,9 @@ namespace {
 //              step's token into the cached lengths (every reader of them in this
 //              step ran in an earlier kernel)
 // ----------------------------------------------------------------------------
-constexpr int FBW = 2, NW = 4, UNROLL = 10;
+// UNROLL k-tiles per batch: 10 weight loads of 1 KiB in flight per wave and 4 workgroups per
+// CU (124 registers) measured better than 20 in flight at 3 per CU
+constexpr int FBW = 2, NW = 4, UNROLL = 5;
 constexpr int kGroupRows = FBW * 32;
 
 struct DecGemvParams {

@@ -139,6 +139,15 @@ def test_mfma_batch_32_and_single_token_prompts():
     gst.destroy()
 
 
+@pytest.mark.parametrize("batch", [1, 3, 5, 9, 17, 31])
+def test_mfma_decode_every_batch_width(batch):
+    # the skinny GEMMs load activations only in the lanes of existing token columns: odd
+    # and one-off widths around the 8 / 16 / 32 boundaries
+    lens = [(7 * b) % 40 + 1 for b in range(batch)]
+    _, gst = run_mfma(SHAPE_G4, 2, lens, 2, 740 + batch, check_kv=False)
+    gst.destroy()
+
+
 def test_mfma_decode_fills_the_cache_to_capacity():
     """70 decode steps from a 58-token prompt: crosses two 32-key block boundaries and a
     decode chunk boundary and ends exactly at max_seq; one more step must be refused."""

@@ -107,6 +107,33 @@ def cpu_baseline(wl, prompt=384, decode=8):
     }
 
 
+def prefill_only_line(name, repeats=20):
+    """Tokens/s of a prefill-only configuration (c2: one block, 4 x 512), timed with events."""
+    import torch
+    import paper_2511_14450_amd as hyp
+    wl = synth.WORKLOADS[name]
+    lens = wl.lengths()
+    T = sum(lens)
+    cfg = hyp.stage_config(wl.shape, len(lens), max(lens), T)
+    stage = hyp.stage_create(cfg, 0, wl.n_layers, device_weights(wl.shape, wl.n_layers, wl.seed))
+    x = device_normal((T, wl.shape.hidden), wl.seed + 1)
+    y = torch.empty_like(x)
+    for _ in range(3):
+        stage.prefill(x, lens, y)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(repeats):
+        stage.prefill(x, lens, y)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / repeats
+    stage.destroy()
+    flops = 2.0 * T * wl.shape.params_per_layer() * wl.n_layers
+    return {"workload": name, "layers": wl.n_layers, "prefill_tokens": T, "prefill_ms": ms,
+            "prefill_tokens_per_s": T / (ms * 1e-3),
+            "prefill_gemm_frac_of_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -252,6 +279,9 @@ def main():
         "mfma_bf16_constant_operands_tflops": hyp.hyp_measure_mfma_ceiling(False),
         "hbm_stream_read_gbs": hyp.hyp_measure_hbm_read_ceiling(4),
     }
+    if args.workload == "c3_stage10" and args.layers <= 0 and args.decode_steps < 0:
+        # the one-block prefill configuration beside the stage (a figure, not the headline value)
+        out["other_configs"] = [prefill_only_line("c2_layer_prefill")]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

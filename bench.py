@@ -134,6 +134,35 @@ def prefill_only_line(name, repeats=20):
             "prefill_gemm_frac_of_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
 
+def gemm_constant_operands_tflops(wl):
+    """TFLOP/s of the gate/up prefill GEMM kernel when every weight and activation is one
+    constant: the same instruction stream as in the timed run, but operands that barely
+    toggle the datapath, so the chip holds its clock.  The gap to the timed run's figure is
+    what the data, not the kernel's schedule, costs."""
+    import torch
+    import paper_2511_14450_amd as hyp
+    shape = wl.shape
+    lens = wl.lengths()
+    T = sum(lens)
+    cfg = hyp.stage_config(shape, len(lens), max(lens), T)
+    w = {n: torch.full(shp, 1.0 if n.endswith("_g") else 0.0078125, dtype=torch.bfloat16, device="cuda")
+         for n, shp in shape.weight_shapes().items()}
+    stage = hyp.stage_create(cfg, 0, 1, [w])
+    del w
+    x = torch.full((T, shape.hidden), 0.5, dtype=torch.bfloat16, device="cuda")
+    y = torch.empty_like(x)
+    for _ in range(2):
+        stage.prefill(x, lens, y)
+    stage.profile(["gemm_gateup"])
+    for _ in range(3):
+        stage.prefill(x, lens, y)
+    torch.cuda.synchronize()
+    ms, n = stage.profile_read("gemm_gateup")
+    stage.profile([])
+    stage.destroy()
+    return 2.0 * T * 2 * shape.ffn_dim * shape.hidden / (ms / n * 1e-3) / 1e12
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -278,6 +307,7 @@ def main():
         "mfma_bf16_gaussian_operands_tflops": hyp.hyp_measure_mfma_ceiling(True),
         "mfma_bf16_constant_operands_tflops": hyp.hyp_measure_mfma_ceiling(False),
         "hbm_stream_read_gbs": hyp.hyp_measure_hbm_read_ceiling(4),
+        "gemm_gateup_kernel_constant_operands_tflops": gemm_constant_operands_tflops(wl),
     }
     if args.workload == "c3_stage10" and args.layers <= 0 and args.decode_steps < 0:
         # the one-block prefill configuration beside the stage (a figure, not the headline value)

@@ -81,7 +81,7 @@ def device_normal(shape, seed):
     return torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16).contiguous()
 
 
-def cpu_baseline(wl, prompt=384, decode=8):
+def cpu_baseline(wl, prompt=1024, decode=16):
     """The oracle as it stands on a bounded sample: ONE block of the workload's
     shape over one request of `prompt` tokens plus `decode` cached steps.  Its
     tokens/s is divided by the stage's block count to be comparable with `value`."""

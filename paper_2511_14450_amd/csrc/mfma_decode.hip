@@ -1,7 +1,8 @@
 // Decode-step kernels of the MFMA path: the weight-streaming skinny GEMM
-// (<= 32 tokens against a [N, K] matrix, bandwidth-bound) and the small kernels
-// that finish its split-K partial sums (RoPE + cache append, SwiGLU), for the
-// KV-cached generation phase of the decoder block of Sec. III-A.
+// (<= 32 tokens against a [N, K] matrix, bandwidth-bound) with its consumers fused
+// into the workgroup that finishes a row group (RoPE + cache append, SwiGLU,
+// residual + next norm), and the kernel that opens a step, for the KV-cached
+// generation phase of the decoder block of Sec. III-A.
 #include "mfma_common.h"
 #include "mfma_kernels.h"
 

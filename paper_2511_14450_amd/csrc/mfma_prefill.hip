@@ -1,6 +1,7 @@
-// MFMA kernels of the prefill path of a bf16 stage: weight repacking, the fused
-// residual-add + RMS Norm, the LDS-staged GEMM with its three epilogues
-// (RoPE + KV-cache write, SwiGLU, plain), for the decoder block of Sec. III-A.
+// MFMA kernels of the prefill path of a bf16 stage: weight repacking, the kernels
+// at the two ends of the residual stream, the LDS-staged GEMM with its four
+// epilogues (RoPE + KV-cache write, SwiGLU, residual add + next RMS Norm's gain
+// and statistics, plain), for the decoder block of Sec. III-A.
 #include "mfma_common.h"
 #include "mfma_kernels.h"
 

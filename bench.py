@@ -170,6 +170,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c3_stage10", choices=[k for k in synth.WORKLOADS if k != "c1_tiny_f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measured ceilings and the other configuration (profiling runs: only the workload's kernels)")
     ap.add_argument("--layers", type=int, default=0, help="override the block count (counter runs on a shorter stage)")
     ap.add_argument("--decode-steps", type=int, default=-1, help="override the number of decode steps")
     ap.add_argument("--no-graph", action="store_true", help="launch decode kernels one by one (for counter runs)")
@@ -303,13 +305,14 @@ def main():
     stage.destroy()
     del stage, x, y
     torch.cuda.empty_cache()
-    out["measured_ceilings"] = {
+    if not args.no_extras:
+      out["measured_ceilings"] = {
         "mfma_bf16_gaussian_operands_tflops": hyp.hyp_measure_mfma_ceiling(True),
         "mfma_bf16_constant_operands_tflops": hyp.hyp_measure_mfma_ceiling(False),
         "hbm_stream_read_gbs": hyp.hyp_measure_hbm_read_ceiling(4),
         "gemm_gateup_kernel_constant_operands_tflops": gemm_constant_operands_tflops(wl),
-    }
-    if args.workload == "c3_stage10" and args.layers <= 0 and args.decode_steps < 0:
+      }
+    if not args.no_extras and args.workload == "c3_stage10" and args.layers <= 0 and args.decode_steps < 0:
         # the one-block prefill configuration beside the stage (a figure, not the headline value)
         out["other_configs"] = [prefill_only_line("c2_layer_prefill")]
     if not args.no_cpu_baseline:

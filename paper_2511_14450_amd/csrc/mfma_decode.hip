@@ -91,7 +91,11 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
       }
     }
   }
-  const int kt0 = (ks * NW + wave) * p.tiles_per_wave;
+  // the workgroup's four waves take the k-tiles of its slice in turn, so that each step of
+  // the workgroup reads 4 KiB contiguous per row block (HBM serves that pattern ~10 % faster
+  // than four separate 1 KiB streams)
+  const int kt0 = ks * NW * p.tiles_per_wave + wave;
+  constexpr size_t kStep = (size_t)NW * kTileElems;
   f32x16_t acc[FBW];
 #pragma unroll
   for (int i = 0; i < FBW; ++i)
@@ -107,7 +111,7 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
-      for (int i = 0; i < FBW; ++i) wf[i][u] = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)(t + u) * kTileElems));
+      for (int i = 0; i < FBW; ++i) wf[i][u] = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)(t + u) * kStep));
     // token columns beyond the batch feed output columns nobody reads: their lanes skip the load
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
@@ -115,7 +119,7 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
       for (int e = 0; e < 8; ++e) xf[u][e] = 0;
     if ((lane & 31) < p.batch) {
 #pragma unroll
-      for (int u = 0; u < UNROLL; ++u) xf[u] = *(const bf16x8_t *)(xp + (size_t)(t + u) * kTileElems);
+      for (int u = 0; u < UNROLL; ++u) xf[u] = *(const bf16x8_t *)(xp + (size_t)(t + u) * kStep);
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
@@ -123,10 +127,10 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
       for (int i = 0; i < FBW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][u], xf[u], acc[i], 0, 0, 0);
   }
   for (; t < p.tiles_per_wave; ++t) {
-    bf16x8_t xf = *(const bf16x8_t *)(xp + (size_t)t * kTileElems);
+    bf16x8_t xf = *(const bf16x8_t *)(xp + (size_t)t * kStep);
 #pragma unroll
     for (int i = 0; i < FBW; ++i) {
-      bf16x8_t wf = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)t * kTileElems));
+      bf16x8_t wf = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)t * kStep));
       acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[i], 0, 0, 0);
     }
   }

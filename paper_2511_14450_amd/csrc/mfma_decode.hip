@@ -67,30 +67,13 @@ struct DecGemvParams {
 };
 
 template <int EPI>
-__global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) k_dec_gemv(DecGemvParams p) {
   __shared__ float red[NW][FBW][16][64];  // 32 KiB; reused as fin[32][65] once reduced
   __shared__ float rstd_s[32];
   __shared__ unsigned is_last;
   float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1]) & red[0][0][0][0];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int fb0 = blockIdx.x * FBW, ks = blockIdx.y;
-  // what the epilogue needs from memory is fetched now, under the streaming loop
-  int pos_pf[4] = {0, 0, 0, 0};  // up to 32 tokens x 32 pairs over 256 threads
-  float cos_pf[4] = {0.f, 0.f, 0.f, 0.f}, sin_pf[4] = {0.f, 0.f, 0.f, 0.f};
-  if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {
-    if (EPI == DEC_QKV) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        int idx = threadIdx.x + j * NW * 64;
-        if (idx < p.batch * 32) {
-          int d0 = ((fb0 >> 1) & 1) * 32 + (idx & 31);
-          pos_pf[j] = p.lens[idx >> 5];
-          cos_pf[j] = p.cos_tab[(size_t)pos_pf[j] * 64 + d0];
-          sin_pf[j] = p.sin_tab[(size_t)pos_pf[j] * 64 + d0];
-        }
-      }
-    }
-  }
   // the workgroup's four waves take the k-tiles of its slice in turn, so that each step of
   // the workgroup reads 4 KiB contiguous per row block (HBM serves that pattern ~10 % faster
   // than four separate 1 KiB streams)
@@ -101,37 +84,48 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
   for (int i = 0; i < FBW; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-  const bf16_t *xp = p.x + (size_t)kt0 * kTileElems + lane * 8;
+  // token columns beyond the batch feed output columns nobody reads: their lanes all read
+  // token 0's chunk, so the x tile costs one cache line more instead of a whole tile
+  const bf16_t *xp = p.x + (size_t)kt0 * kTileElems + ((lane & 31) < p.batch ? lane : (lane & 32)) * 8;
   const bf16_t *wp[FBW];
 #pragma unroll
   for (int i = 0; i < FBW; ++i) wp[i] = p.W + ((size_t)(fb0 + i) * p.KT + kt0) * kTileElems + lane * 8;
+  // A window of UNROLL k-tiles lives in registers; as soon as a tile has gone through the
+  // MFMAs its registers are reloaded with the tile UNROLL further on, so the wave keeps
+  // about 2 (UNROLL - 1) KiB of weights in flight all the time.
+  bf16x8_t xf[UNROLL], wf[FBW][UNROLL];
+  auto load_tile = [&](int u, int tile) {
+#pragma unroll
+    for (int i = 0; i < FBW; ++i) wf[i][u] = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)tile * kStep));
+    xf[u] = *(const bf16x8_t *)(xp + (size_t)tile * kStep);
+  };
+  auto use_tile = [&](int u) {
+#pragma unroll
+    for (int i = 0; i < FBW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][u], xf[u], acc[i], 0, 0, 0);
+  };
+  const int n_win = p.tiles_per_wave / UNROLL;  // short K slices (n_win == 0) go through the tail loop only
   int t = 0;
-  for (; t + UNROLL <= p.tiles_per_wave; t += UNROLL) {
-    bf16x8_t xf[UNROLL], wf[FBW][UNROLL];
+  if (n_win > 0) {
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
+    for (int u = 0; u < UNROLL; ++u) load_tile(u, u);
+    for (int wi = 1; wi < n_win; ++wi, t += UNROLL) {
 #pragma unroll
-      for (int i = 0; i < FBW; ++i) wf[i][u] = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)(t + u) * kStep));
-    // token columns beyond the batch feed output columns nobody reads: their lanes skip the load
-#pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) xf[u][e] = 0;
-    if ((lane & 31) < p.batch) {
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u) xf[u] = *(const bf16x8_t *)(xp + (size_t)(t + u) * kStep);
+      for (int u = 0; u < UNROLL; ++u) {
+        use_tile(u);
+        load_tile(u, t + UNROLL + u);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
-#pragma unroll
-      for (int i = 0; i < FBW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][u], xf[u], acc[i], 0, 0, 0);
+    for (int u = 0; u < UNROLL; ++u) use_tile(u);
+    t += UNROLL;
   }
   for (; t < p.tiles_per_wave; ++t) {
-    bf16x8_t xf = *(const bf16x8_t *)(xp + (size_t)t * kStep);
+    bf16x8_t x1 = *(const bf16x8_t *)(xp + (size_t)t * kStep);
 #pragma unroll
     for (int i = 0; i < FBW; ++i) {
-      bf16x8_t wf = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)t * kStep));
-      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[i], 0, 0, 0);
+      bf16x8_t w1 = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)t * kStep));
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, x1, acc[i], 0, 0, 0);
     }
   }
 #pragma unroll
@@ -180,6 +174,21 @@ __global__ void __launch_bounds__(NW * 64) k_dec_gemv(DecGemvParams p) {
   // The finishing workgroup.  Its loads are issued together so that their round trips
   // overlap: first the sums of squares behind the RMS Norm factor (16 row groups per
   // thread at once), then the partial sums.
+  // what the QKV epilogue needs from memory is requested together with the loads below
+  int pos_pf[4] = {0, 0, 0, 0};  // up to 32 tokens x 32 pairs over 256 threads
+  float cos_pf[4] = {0.f, 0.f, 0.f, 0.f}, sin_pf[4] = {0.f, 0.f, 0.f, 0.f};
+  if (EPI == DEC_QKV) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int idx = threadIdx.x + j * NW * 64;
+      if (idx < p.batch * 32) {
+        int d0 = ((fb0 >> 1) & 1) * 32 + (idx & 31);
+        pos_pf[j] = p.lens[idx >> 5];
+        cos_pf[j] = p.cos_tab[(size_t)pos_pf[j] * 64 + d0];
+        sin_pf[j] = p.sin_tab[(size_t)pos_pf[j] * 64 + d0];
+      }
+    }
+  }
   float ssq_v[16];
   const int ssq_tkn = threadIdx.x & 31, ssq_part_id = threadIdx.x >> 5;
   if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {

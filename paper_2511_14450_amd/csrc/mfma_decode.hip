@@ -74,6 +74,17 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
   float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1]) & red[0][0][0][0];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int fb0 = blockIdx.x * FBW, ks = blockIdx.y;
+  // positions of the step's tokens (the QKV epilogue's rotary angles depend on them): fetched under the streaming loop
+  // (ahead of time for the first kPf * 8 tokens, which covers the usual batch; the rest is loaded in place)
+  constexpr int kPf = 2;
+  int pos_pf[kPf] = {0, 0};
+  if (EPI == DEC_QKV) {
+#pragma unroll
+    for (int j = 0; j < kPf; ++j) {
+      int idx = threadIdx.x + j * NW * 64;
+      if (idx < p.batch * 32) pos_pf[j] = p.lens[idx >> 5];
+    }
+  }
   // the workgroup's four waves take the k-tiles of its slice in turn, so that each step of
   // the workgroup reads 4 KiB contiguous per row block (HBM serves that pattern ~10 % faster
   // than four separate 1 KiB streams)
@@ -174,18 +185,31 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
   // The finishing workgroup.  Its loads are issued together so that their round trips
   // overlap: first the sums of squares behind the RMS Norm factor (16 row groups per
   // thread at once), then the partial sums.
-  // what the QKV epilogue needs from memory is requested together with the loads below
-  int pos_pf[4] = {0, 0, 0, 0};  // up to 32 tokens x 32 pairs over 256 threads
-  float cos_pf[4] = {0.f, 0.f, 0.f, 0.f}, sin_pf[4] = {0.f, 0.f, 0.f, 0.f};
+  // what the epilogues need from memory besides the partial sums is requested first, so that
+  // all of a finisher's loads share one round trip
+  float cos_pf[kPf] = {0.f, 0.f}, sin_pf[kPf] = {0.f, 0.f};
   if (EPI == DEC_QKV) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kPf; ++j) {
       int idx = threadIdx.x + j * NW * 64;
       if (idx < p.batch * 32) {
         int d0 = ((fb0 >> 1) & 1) * 32 + (idx & 31);
-        pos_pf[j] = p.lens[idx >> 5];
         cos_pf[j] = p.cos_tab[(size_t)pos_pf[j] * 64 + d0];
         sin_pf[j] = p.sin_tab[(size_t)pos_pf[j] * 64 + d0];
+      }
+    }
+  }
+  constexpr int kPfR = 4;  // (token, row) pairs per thread fetched ahead: 16 tokens' worth
+  float xres_pf[kPfR], gain_pf[kPfR];  // residual stream and next norm's gain
+  if (EPI == DEC_RESID || EPI == DEC_FINAL) {
+#pragma unroll
+    for (int j = 0; j < kPfR; ++j) {
+      int idx = threadIdx.x + j * NW * 64;
+      xres_pf[j] = 0.f; gain_pf[j] = 0.f;
+      if (idx < n_pairs) {
+        int f = idx % kGroupRows, b = idx / kGroupRows;
+        xres_pf[j] = p.xres[(size_t)b * p.H + fb0 * 32 + f];
+        if (EPI == DEC_RESID) gain_pf[j] = bf16_to_f32(p.gain[fb0 * 32 + f]);
       }
     }
   }
@@ -204,24 +228,27 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     // and nothing in this launch read these lines before, so a line is either
     // absent (fetched from memory, where the writer's store has completed) or was
     // put there by a writer on this very XCD.  Two (token, row) pairs per thread and
-    // eight slices of each are in flight at once; slices beyond ksplit are masked
-    // rather than peeled, so the gather costs ceil(ksplit / 8) round trips.
+    // GW slices of each are in flight at once; slices beyond ksplit are masked
+    // rather than peeled, so the gather costs ceil(ksplit / GW) round trips.
+    constexpr int GW = EPI == DEC_QKV ? 8 : 16;
     for (int idx0 = threadIdx.x; idx0 < n_pairs; idx0 += 2 * NW * 64) {
       const int idx1 = idx0 + NW * 64;
       const bool has1 = idx1 < n_pairs;
-      const float *src0 = p.partial + (size_t)(idx0 / kGroupRows) * p.N + fb0 * 32 + idx0 % kGroupRows;
-      const float *src1 = p.partial + (size_t)((has1 ? idx1 : idx0) / kGroupRows) * p.N + fb0 * 32 + (has1 ? idx1 : idx0) % kGroupRows;
+      // slice bases are uniform (scalar registers); one 32-bit offset per pair serves every slice
+      const unsigned off0 = (unsigned)((idx0 / kGroupRows) * p.N + fb0 * 32 + idx0 % kGroupRows);
+      const unsigned off1 = (unsigned)(((has1 ? idx1 : idx0) / kGroupRows) * p.N + fb0 * 32 + (has1 ? idx1 : idx0) % kGroupRows);
       float sum0 = 0.f, sum1 = 0.f;
-      for (int s = 0; s < p.ksplit; s += 8) {
-        float v0[8], v1[8];
+      for (int s = 0; s < p.ksplit; s += GW) {
+        float v0[GW], v1[GW];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < GW; ++u) {
           const bool in = s + u < p.ksplit;
-          v0[u] = in ? src0[(size_t)(s + u) * 32 * p.N] : 0.f;
-          v1[u] = in && has1 ? src1[(size_t)(s + u) * 32 * p.N] : 0.f;
+          const float *slice = p.partial + (size_t)(s + u) * 32 * p.N;
+          v0[u] = in ? slice[off0] : 0.f;
+          v1[u] = in && has1 ? slice[off1] : 0.f;
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { sum0 += v0[u]; sum1 += v1[u]; }
+        for (int u = 0; u < GW; ++u) { sum0 += v0[u]; sum1 += v1[u]; }
       }
       fin[idx0 / kGroupRows][idx0 % kGroupRows] = sum0;
       if (has1) fin[idx1 / kGroupRows][idx1 % kGroupRows] = sum1;
@@ -257,9 +284,10 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
       int x = idx & 31, b = idx >> 5;
       float a = fin[b][x] * rstd_s[b], c = fin[b][32 + x] * rstd_s[b];
       int d0 = w * 32 + x, d1 = d0 + 64;
-      int pos = pos_pf[j];
+      int pos = j < kPf ? pos_pf[j] : p.lens[b];
       if (head < p.nq + p.nkv) {
-        float cs = cos_pf[j], sn = sin_pf[j];
+        float cs = j < kPf ? cos_pf[j] : p.cos_tab[(size_t)pos * 64 + d0];
+        float sn = j < kPf ? sin_pf[j] : p.sin_tab[(size_t)pos * 64 + d0];
         float lo = a * cs - c * sn, hi = c * cs + a * sn;
         if (head < p.nq) {
           int G = p.nq / p.nkv;
@@ -288,12 +316,15 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     }
   } else {
     const int n0 = fb0 * 32;
-    for (int idx = threadIdx.x; idx < n_pairs; idx += NW * 64) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      int idx = threadIdx.x + j * NW * 64;
+      if (idx >= n_pairs) break;
       int f = idx % kGroupRows, b = idx / kGroupRows;
-      float xn = p.xres[(size_t)b * p.H + n0 + f] + fin[b][f];
+      float xn = (j < kPfR ? xres_pf[j] : p.xres[(size_t)b * p.H + n0 + f]) + fin[b][f];
       if (EPI == DEC_RESID) {
         p.xres[(size_t)b * p.H + n0 + f] = xn;
-        p.y_out[frag_offset(b, n0 + f, p.H)] = f2bf_dev(xn * bf16_to_f32(p.gain[n0 + f]));
+        p.y_out[frag_offset(b, n0 + f, p.H)] = f2bf_dev(xn * (j < kPfR ? gain_pf[j] : bf16_to_f32(p.gain[n0 + f])));
         fin[b][f] = xn * xn;
       } else {
         p.hidden_out[(size_t)b * p.H + n0 + f] = f2bf_dev(xn);

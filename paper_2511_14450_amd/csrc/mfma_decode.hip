@@ -41,6 +41,7 @@ namespace {
 // CU (124 registers) measured better than 20 in flight at 3 per CU
 constexpr int FBW = 2, NW = 4, UNROLL = 5;
 constexpr int kGroupRows = FBW * 32;
+constexpr int kRedStride = kGroupRows + 4;  // keeps 16-byte alignment, spreads tokens over banks
 
 struct DecGemvParams {
   const bf16_t *W, *x;
@@ -68,10 +69,12 @@ struct DecGemvParams {
 
 template <int EPI>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) k_dec_gemv(DecGemvParams p) {
-  __shared__ float red[NW][FBW][16][64];  // 32 KiB; reused as fin[32][65] once reduced
+  // the waves' sums as [wave][token][row]: rows contiguous so that the cross-wave add reads
+  // without bank conflicts; 34 KiB, reused as fin[32][65] once reduced
+  __shared__ __attribute__((aligned(16))) float red[NW][32][kRedStride];
   __shared__ float rstd_s[32];
   __shared__ unsigned is_last;
-  float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1]) & red[0][0][0][0];
+  float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1]) & red[0][0][0];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int fb0 = blockIdx.x * FBW, ks = blockIdx.y;
   // positions of the step's tokens (the QKV epilogue's rotary angles depend on them): fetched under the streaming loop
@@ -139,13 +142,19 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
       acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, x1, acc[i], 0, 0, 0);
     }
   }
+  // accumulator register r of lane l of block i is packed row 32 i + 8 (r/4) + 4 (l/32) + r%4 of
+  // token l % 32: four consecutive rows per 16-byte store; token columns beyond the batch stay home
+  if ((lane & 31) < p.batch) {
 #pragma unroll
-  for (int i = 0; i < FBW; ++i)
+    for (int i = 0; i < FBW; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) red[wave][i][r][lane] = acc[i][r];
+      for (int q = 0; q < 4; ++q) {
+        f32x4_t v = {acc[i][4 * q], acc[i][4 * q + 1], acc[i][4 * q + 2], acc[i][4 * q + 3]};
+        *(f32x4_t *)&red[wave][lane & 31][32 * i + 8 * q + 4 * (lane >> 5)] = v;
+      }
+  }
   __syncthreads();
-  // sums of the 64 rows of this group: accumulator register r of lane l of block i is
-  // packed row 32 i + 8 (r/4) + 4 (l/32) + r%4, token l % 32.  At most 8 per thread.
+  // sums of the 64 rows of this group, at most 8 (token, row) pairs per thread
   const int n_pairs = p.batch * kGroupRows;
   float mine[8];
 #pragma unroll
@@ -154,10 +163,8 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     mine[j] = 0.f;
     if (idx < n_pairs) {
       int f = idx % kGroupRows, token = idx / kGroupRows;
-      int i = f >> 5, fl = f & 31;
-      int r = ((fl >> 3) << 2) + (fl & 3), l = (((fl >> 2) & 1) << 5) + token;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) mine[j] += red[w][i][r][l];
+      for (int w = 0; w < NW; ++w) mine[j] += red[w][token][f];
     }
   }
   __syncthreads();  // `red` is free from here on

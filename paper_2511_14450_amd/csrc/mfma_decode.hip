@@ -41,6 +41,7 @@ namespace {
 // CU (124 registers) measured better than 20 in flight at 3 per CU
 constexpr int FBW = 2, NW = 4, UNROLL = 5;
 constexpr int kGroupRows = FBW * 32;
+constexpr int kSsqParts = NW * 2;  // interleaved partial sums of the row groups' sums of squares (one per 32 threads)
 constexpr int kRedStride = kGroupRows + 4;  // keeps 16-byte alignment, spreads tokens over banks
 
 struct DecGemvParams {
@@ -117,9 +118,9 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
 #pragma unroll
     for (int i = 0; i < FBW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][u], xf[u], acc[i], 0, 0, 0);
   };
-  const int n_win = p.tiles_per_wave / UNROLL;  // short K slices (n_win == 0) go through the tail loop only
-  int t = 0;
+  const int n_win = p.tiles_per_wave / UNROLL, rem = p.tiles_per_wave - n_win * UNROLL;
   if (n_win > 0) {
+    int t = 0;
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) load_tile(u, u);
     for (int wi = 1; wi < n_win; ++wi, t += UNROLL) {
@@ -130,18 +131,20 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // last full window; the rem (< UNROLL) tiles left over move into its registers as they free up
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) use_tile(u);
-    t += UNROLL;
-  }
-  for (; t < p.tiles_per_wave; ++t) {
-    bf16x8_t x1 = *(const bf16x8_t *)(xp + (size_t)t * kStep);
-#pragma unroll
-    for (int i = 0; i < FBW; ++i) {
-      bf16x8_t w1 = __builtin_nontemporal_load((const bf16x8_t *)(wp[i] + (size_t)t * kStep));
-      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, x1, acc[i], 0, 0, 0);
+    for (int u = 0; u < UNROLL; ++u) {
+      use_tile(u);
+      if (u < rem) load_tile(u, t + UNROLL + u);
     }
+  } else {
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (u < rem) load_tile(u, u);
   }
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u)
+    if (u < rem) use_tile(u);
   // accumulator register r of lane l of block i is packed row 32 i + 8 (r/4) + 4 (l/32) + r%4 of
   // token l % 32: four consecutive rows per 16-byte store; token columns beyond the batch stay home
   if ((lane & 31) < p.batch) {
@@ -225,7 +228,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
   if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      int g = ssq_part_id + 8 * u;
+      int g = ssq_part_id + kSsqParts * u;
       ssq_v[u] = g < p.n_ssq ? p.ssq_in[g * 32 + ssq_tkn] : 0.f;
     }
   }
@@ -263,19 +266,19 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
   }
   if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {
     // RMS Norm factor of every token: the row groups' sums of squares, added in a
-    // fixed order (8 interleaved partial sums, then those in order)
-    __shared__ float ssq_part[8][32];
+    // fixed order (kSsqParts interleaved partial sums, then those in order)
+    __shared__ float ssq_part[kSsqParts][32];
     {
       float ss = 0.f;
 #pragma unroll
       for (int u = 0; u < 16; ++u) ss += ssq_v[u];
-      for (int g = ssq_part_id + 8 * 16; g < p.n_ssq; g += 8) ss += p.ssq_in[g * 32 + ssq_tkn];
+      for (int g = ssq_part_id + kSsqParts * 16; g < p.n_ssq; g += kSsqParts) ss += p.ssq_in[g * 32 + ssq_tkn];
       ssq_part[ssq_part_id][ssq_tkn] = ss;
     }
     __syncthreads();
     if (threadIdx.x < 32) {
       float ss = 0.f;
-      for (int i = 0; i < 8; ++i) ss += ssq_part[i][threadIdx.x];
+      for (int i = 0; i < kSsqParts; ++i) ss += ssq_part[i][threadIdx.x];
       rstd_s[threadIdx.x] = 1.0f / sqrtf(ss * p.inv_H + p.eps);
     }
   }
@@ -397,19 +400,21 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 
 }  // namespace
 
-// K slices across workgroups: about 10 or more tiles per wave, no more
-// workgroups than keep the chip busy a few times over, and few enough slices
-// that the fp32 partial sums (written and read once per slice and token) stay
-// near a tenth of the weight bytes
+// K slices across workgroups: the fewest that bring a wave's share down to about 56 k-tiles
+// (measured on the Phi-3-medium shapes: longer shares leave too few waves to cover the memory
+// latency, shorter ones pay more in partial sums, counters and finishing workgroups than
+// they win), and few enough that the fp32 partial sums (written and read once per slice and
+// token) stay a small fraction of the weight bytes
 int mfma_gemv_ksplit(int N, int K, int batch) {
-  int KT = K / 16, groups = N / kGroupRows;
+  (void)N;
+  int KT = K / 16;
   int cap = (int)(0.025 * K / (batch > 0 ? batch : 1));
   if (cap < 1) cap = 1;
   int best = 1;
   for (int ks = 1; ks <= 64 && ks <= cap; ++ks) {
     if (KT % (ks * NW) != 0) continue;
-    if (KT / (ks * NW) < 10 || groups * ks > 2400) break;
     best = ks;
+    if (KT / (ks * NW) <= 56) break;
   }
   return best;
 }

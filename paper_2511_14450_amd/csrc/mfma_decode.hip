@@ -237,31 +237,51 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     // writer in this launch, this XCD's L2 was invalidated when the launch began,
     // and nothing in this launch read these lines before, so a line is either
     // absent (fetched from memory, where the writer's store has completed) or was
-    // put there by a writer on this very XCD.  Two (token, row) pairs per thread and
-    // GW slices of each are in flight at once; slices beyond ksplit are masked
+    // put there by a writer on this very XCD.  With more than four slices, two (token, row)
+    // pairs per thread and GW slices of each are in flight at once; slices beyond ksplit are masked
     // rather than peeled, so the gather costs ceil(ksplit / GW) round trips.
     constexpr int GW = EPI == DEC_QKV ? 8 : 16;
-    for (int idx0 = threadIdx.x; idx0 < n_pairs; idx0 += 2 * NW * 64) {
-      const int idx1 = idx0 + NW * 64;
-      const bool has1 = idx1 < n_pairs;
-      // slice bases are uniform (scalar registers); one 32-bit offset per pair serves every slice
-      const unsigned off0 = (unsigned)((idx0 / kGroupRows) * p.N + fb0 * 32 + idx0 % kGroupRows);
-      const unsigned off1 = (unsigned)(((has1 ? idx1 : idx0) / kGroupRows) * p.N + fb0 * 32 + (has1 ? idx1 : idx0) % kGroupRows);
-      float sum0 = 0.f, sum1 = 0.f;
-      for (int s = 0; s < p.ksplit; s += GW) {
-        float v0[GW], v1[GW];
+    if (p.ksplit <= 4) {
+      // few slices: four of the thread's pairs at once (16 tokens' worth per round trip)
+      for (int j0 = 0; j0 * NW * 64 < n_pairs; j0 += 4) {
+        float v[4][4];
 #pragma unroll
-        for (int u = 0; u < GW; ++u) {
-          const bool in = s + u < p.ksplit;
-          const float *slice = p.partial + (size_t)(s + u) * 32 * p.N;
-          v0[u] = in ? slice[off0] : 0.f;
-          v1[u] = in && has1 ? slice[off1] : 0.f;
+        for (int j = 0; j < 4; ++j) {
+          const int idx = threadIdx.x + (j0 + j) * NW * 64;
+          const bool has = idx < n_pairs;
+          const unsigned off = has ? (unsigned)((idx / kGroupRows) * p.N + fb0 * 32 + idx % kGroupRows) : 0u;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[j][u] = has && u < p.ksplit ? (p.partial + (size_t)u * 32 * p.N)[off] : 0.f;
         }
 #pragma unroll
-        for (int u = 0; u < GW; ++u) { sum0 += v0[u]; sum1 += v1[u]; }
+        for (int j = 0; j < 4; ++j) {
+          const int idx = threadIdx.x + (j0 + j) * NW * 64;
+          if (idx < n_pairs) fin[idx / kGroupRows][idx % kGroupRows] = ((v[j][0] + v[j][1]) + v[j][2]) + v[j][3];
+        }
       }
-      fin[idx0 / kGroupRows][idx0 % kGroupRows] = sum0;
-      if (has1) fin[idx1 / kGroupRows][idx1 % kGroupRows] = sum1;
+    } else {
+      for (int idx0 = threadIdx.x; idx0 < n_pairs; idx0 += 2 * NW * 64) {
+        const int idx1 = idx0 + NW * 64;
+        const bool has1 = idx1 < n_pairs;
+        // slice bases are uniform (scalar registers); one 32-bit offset per pair serves every slice
+        const unsigned off0 = (unsigned)((idx0 / kGroupRows) * p.N + fb0 * 32 + idx0 % kGroupRows);
+        const unsigned off1 = (unsigned)(((has1 ? idx1 : idx0) / kGroupRows) * p.N + fb0 * 32 + (has1 ? idx1 : idx0) % kGroupRows);
+        float sum0 = 0.f, sum1 = 0.f;
+        for (int s = 0; s < p.ksplit; s += GW) {
+          float v0[GW], v1[GW];
+#pragma unroll
+          for (int u = 0; u < GW; ++u) {
+            const bool in = s + u < p.ksplit;
+            const float *slice = p.partial + (size_t)(s + u) * 32 * p.N;
+            v0[u] = in ? slice[off0] : 0.f;
+            v1[u] = in && has1 ? slice[off1] : 0.f;
+          }
+#pragma unroll
+          for (int u = 0; u < GW; ++u) { sum0 += v0[u]; sum1 += v1[u]; }
+        }
+        fin[idx0 / kGroupRows][idx0 % kGroupRows] = sum0;
+        if (has1) fin[idx1 / kGroupRows][idx1 % kGroupRows] = sum1;
+      }
     }
   }
   if (EPI == DEC_QKV || EPI == DEC_SWIGLU) {

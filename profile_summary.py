@@ -33,8 +33,8 @@ CLASS_OF = [  # (regex on the kernel name, grid-x test, class)
 # kernels shared by two classes, told apart by their launch size on the c3 workload
 # (total work-items): the decode O / down projections differ in ksplit
 NAME_BY_GRID = {
-    "k_dec_gemv<2>/grid163840": "gemv_o", "k_dec_gemv<3>/grid573440": "gemv_down",
-    "k_dec_gemv<2>/grid573440": "gemv_down",
+    "k_dec_gemv<2>/grid40960": "gemv_o", "k_dec_gemv<3>/grid102400": "gemv_down",
+    "k_dec_gemv<2>/grid102400": "gemv_down",
 }
 
 

@@ -3,6 +3,7 @@
 // attention of one new token per request against the cache (bandwidth-bound).
 // Both follow the GQA-with-RoPE sub-layer of Sec. III-A; RoPE was already
 // applied to q and to the cached keys by the QKV epilogue.
+#include <type_traits>
 #include "mfma_common.h"
 #include "mfma_kernels.h"
 
@@ -173,6 +174,7 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
 // ----------------------------------------------------------------------------
 constexpr int kPartStride = 130;
 
+template <int NSETS>
 __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ qdec,
                                                     const bf16_t *__restrict__ Kc,
                                                     const bf16_t *__restrict__ Vc, CacheGeom geom,
@@ -200,7 +202,7 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  bf16x8_t kA[8], vA[8], kB[8], vB[8];
+  bf16x8_t kS[NSETS][8], vS[NSETS][8];
   auto load_block = [&](int kb, bf16x8_t *kf, bf16x8_t *vf) {
     const bf16_t *kblk = Kc + geom.off(req, kvh, kb) + lane * 8;
     const bf16_t *vblk = Vc + geom.off(req, kvh, kb) + lane * 8;
@@ -256,15 +258,45 @@ __global__ void __launch_bounds__(64) k_attn_decode(const bf16_t *__restrict__ q
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[4 + db], pf1, o[db], 0, 0, 0);
     }
   };
-  // two register sets: the loads of the next block are in flight while this one is used
-  load_block(kb_begin, kA, vA);
-  for (int kb = kb_begin; kb < kb_end; kb += 2) {
-    if (kb + 1 < kb_end) load_block(kb + 1, kB, vB);
-    compute_block(kb, kA, vA);
-    if (kb + 1 < kb_end) {
-      if (kb + 2 < kb_end) load_block(kb + 2, kA, vA);
-      compute_block(kb + 1, kB, vB);
+  // NSETS register sets: the loads of the next NSETS - 1 blocks are in flight while one is used.
+  // Block kb_begin + j lives in set j % NSETS.  No load sits under a condition between two
+  // uses: the compiler counts outstanding loads per path, and a load that may or may not have
+  // been issued makes it wait for everything.  So: a steady loop of whole groups of NSETS
+  // blocks, then one of NSETS straight-line endings chosen by the number of loads still to issue.
+  const int n = kb_end - kb_begin;
+  if (n < NSETS - 1) {
+    for (int j = 0; j < n; ++j) {
+      load_block(kb_begin + j, kS[0], vS[0]);
+      compute_block(kb_begin + j, kS[0], vS[0]);
     }
+  } else {
+#pragma unroll
+    for (int u = 0; u < NSETS - 1; ++u) load_block(kb_begin + u, kS[u], vS[u]);
+    int i = 0;
+    for (; i + 2 * NSETS - 1 <= n; i += NSETS) {
+#pragma unroll
+      for (int u = 0; u < NSETS; ++u) {
+        load_block(kb_begin + i + u + NSETS - 1, kS[(u + NSETS - 1) % NSETS], vS[(u + NSETS - 1) % NSETS]);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_block(kb_begin + i + u, kS[u], vS[u]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    const int r = n - (i + NSETS - 1);  // loads still to issue, 0 .. NSETS - 1
+    auto ending = [&](auto R) {
+      constexpr int kR = decltype(R)::value;
+#pragma unroll
+      for (int u = 0; u < kR + NSETS - 1; ++u) {
+        if (u < kR) load_block(kb_begin + i + u + NSETS - 1, kS[(u + NSETS - 1) % NSETS], vS[(u + NSETS - 1) % NSETS]);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_block(kb_begin + i + u, kS[u % NSETS], vS[u % NSETS]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    if (r == 0) ending(std::integral_constant<int, 0>());
+    else if (r == 1) ending(std::integral_constant<int, 1>());
+    else if (r == 2 || NSETS < 4) ending(std::integral_constant<int, NSETS < 3 ? 1 : 2>());
+    else ending(std::integral_constant<int, NSETS < 4 ? 1 : 3>());
   }
   // lanes tl < G hold real heads
   float l_tot = xhalf_sum(l_run);
@@ -336,7 +368,7 @@ hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *
                             const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
                             int max_chunks, int chunk_keys, hipStream_t s) {
   int G = nq / nkv;
-  k_attn_decode<<<dim3(max_chunks, nkv, batch), 64, 0, s>>>(qdec, Kc, Vc, geom, lens, part, nq, G, max_chunks, chunk_keys);
+  k_attn_decode<2><<<dim3(max_chunks, nkv, batch), 64, 0, s>>>(qdec, Kc, Vc, geom, lens, part, nq, G, max_chunks, chunk_keys);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   k_attn_decode_merge<<<dim3(nq, batch), 128, 0, s>>>(part, lens, out, nq, max_chunks, chunk_keys);

@@ -148,6 +148,20 @@ def test_mfma_decode_every_batch_width(batch):
     gst.destroy()
 
 
+# K = 4096 is the smallest width here whose skinny GEMMs are split along K across workgroups
+# (two slices for QKV, O and gate/up; the K = 1024 down projection stays unsplit)
+SHAPE_SPLITK = synth.BlockShape(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=1024, dtype="bf16")
+
+
+@pytest.mark.parametrize("batch", [3, 17, 31])
+def test_mfma_decode_split_k_at_odd_batch_widths(batch):
+    # partial sums, arrival counters and the finishing workgroup's gather with 3, 17 and 31
+    # live token columns (one, five and eight (token, row) pairs per finishing thread)
+    lens = [(5 * b) % 9 + 1 for b in range(batch)]
+    _, gst = run_mfma(SHAPE_SPLITK, 1, lens, 2, 760 + batch, sigma=0.02, check_kv=False)
+    gst.destroy()
+
+
 def test_mfma_decode_fills_the_cache_to_capacity():
     """70 decode steps from a 58-token prompt: crosses two 32-key block boundaries and a
     decode chunk boundary and ends exactly at max_seq; one more step must be refused."""

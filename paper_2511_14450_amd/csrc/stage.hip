@@ -637,7 +637,9 @@ hyp_status_t stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t
     }
     // causal attention work grows with a tile's position in its request: longest tiles first,
     // so that the launch ends on short ones
-    std::stable_sort(h_tiles, h_tiles + nt, [](const PrefillTile &a, const PrefillTile &b) { return a.qblk0 > b.qblk0; });
+    std::sort(h_tiles, h_tiles + nt, [](const PrefillTile &a, const PrefillTile &b) {
+      return a.qblk0 != b.qblk0 ? a.qblk0 > b.qblk0 : a.row0 < b.row0;  // total order, in place
+    });
     for (int i = 0; i < 32; ++i) h_ext_dec[i] = i < batch ? i : -1;
     HIP_TRY(st, hipMemcpyAsync(st->ws + L.row_ext, h_ext, sizeof(int) * R, hipMemcpyHostToDevice, s));
     HIP_TRY(st, hipMemcpyAsync(st->ws + L.row_pos, h_pos, sizeof(int) * R, hipMemcpyHostToDevice, s));

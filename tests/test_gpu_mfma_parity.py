@@ -162,6 +162,26 @@ def test_mfma_decode_split_k_at_odd_batch_widths(batch):
     gst.destroy()
 
 
+def test_mfma_split_k_decode_is_run_to_run_identical():
+    # whichever workgroup of a row group arrives last adds the K slices in slice order:
+    # eight repetitions of the same steps must agree bit for bit
+    import torch
+    shape = SHAPE_SPLITK
+    layers = [synth.layer_weights(shape, 0, 770, sigma=0.02)]
+    st = make_gpu_stage(shape, layers, 5, 64, 64)
+    x = to_dev(synth.hidden_states(40, shape, 771), "bf16")
+    xd = [to_dev(synth.hidden_states(5, shape, 772 + i), "bf16") for i in range(3)]
+    ref = None
+    for rep in range(8):
+        st.prefill(x, [3, 11, 7, 9, 10])
+        outs = [st.decode_step(d).clone() for d in xd]
+        if ref is None:
+            ref = outs
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(ref, outs)), rep
+    st.destroy()
+
+
 def test_mfma_decode_fills_the_cache_to_capacity():
     """70 decode steps from a 58-token prompt: crosses two 32-key block boundaries and a
     decode chunk boundary and ends exactly at max_seq; one more step must be refused."""

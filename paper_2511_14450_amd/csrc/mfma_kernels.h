@@ -25,7 +25,13 @@ struct GemmEpilogue {
   const bf16_t *gain = nullptr;
   const int *row_ext = nullptr;
   float *ssq_part = nullptr;
+  // any epilogue: scratch for GEMMs whose K loop is split across workgroups (few output tiles)
+  float *split_ws = nullptr;          // mfma_gemm_split_ws_bytes()
+  unsigned *split_counters = nullptr;  // kGemmSplitMaxTiles, zero between launches
 };
+
+constexpr int kGemmSplitMaxTiles = 255;  // GEMMs with at least a round of output tiles are never split
+size_t mfma_gemm_split_ws_bytes();
 
 // dst = P(N, K) of the row-permuted concatenation [src0; src1; src2]
 hipError_t mfma_pack_weight(const bf16_t *src0, const bf16_t *src1, const bf16_t *src2, int rows0,

@@ -171,6 +171,10 @@ struct GemmParams {
   const bf16_t *gain;
   const int *row_ext;
   float *ssq_part;                 // [N / 64][T']
+  // K loop split over `ksplit` workgroups per tile (GEMMs with few tiles): fp32 partial tiles and arrival counters
+  int ksplit, tiles_grid;
+  float *split_ws;
+  unsigned *split_counters;
 };
 
 __device__ __forceinline__ void store_block(bf16_t *out, int out_K, int tb, int f0, int lane,
@@ -190,7 +194,8 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wf = wave / WT, wt = wave % WT;
   // tile of this workgroup
-  int nwg = gridDim.x, id = blockIdx.x;
+  __shared__ unsigned split_last;
+  const int nwg = p.tiles_grid, id = blockIdx.x % p.tiles_grid, slice = blockIdx.x / p.tiles_grid;
   int q = (id % 8) * (nwg / 8) + id / 8;
   if (q >= p.n_tiles) return;
   const int tiles_n = p.feat_blocks / NBK;
@@ -210,17 +215,18 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nsteps = KT / KTS;  // >= NST guaranteed by the host
+  const int nsteps = KT / KTS / p.ksplit;  // stages of this workgroup's K slice, >= NST guaranteed by the host
+  const size_t k_first = (size_t)slice * nsteps * KTS * kTileElems;
   const bf16_t *src[LPW];
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
     int lid = wave * LPW + i;
     int blk = lid / KTS, kt = lid % KTS;
     if (blk >= XB) {
-      src[i] = p.W + ((size_t)(nb0 + blk - XB) * KT + kt) * kTileElems + lane * 8;
+      src[i] = p.W + ((size_t)(nb0 + blk - XB) * KT + kt) * kTileElems + lane * 8 + k_first;
     } else {
       int tb = min(tb0 + blk, p.tok_blocks - 1);  // tail tile: reread the last block
-      src[i] = p.X + ((size_t)tb * KT + kt) * kTileElems + lane * 8;
+      src[i] = p.X + ((size_t)tb * KT + kt) * kTileElems + lane * 8 + k_first;
     }
   }
   auto issue1 = [&](int i, int step, int buf) {
@@ -299,6 +305,59 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the tail refills before the wave ends
+
+  // ------------------------------------------------------------------ split K: the last workgroup of a tile adds up
+  if (p.ksplit > 1) {
+    // Every workgroup of a tile leaves its fp32 accumulators of the live token blocks in the
+    // scratch area (write-through stores, completed before its arrival is counted); the one
+    // that arrives last reads all slices back in slice order - so the sum does not depend on
+    // which one that is - and goes on to the epilogue.  Plain loads suffice: every line has one
+    // writer in this launch and no reader before the counter says so.
+    float *mine = p.split_ws + (((size_t)q * p.ksplit + slice) * (WF * WT) + wave) * (FB * TB * 16 * 64);
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      if (tb0 + wt * TB + j >= p.tok_blocks) continue;
+#pragma unroll
+      for (int i = 0; i < FB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          __hip_atomic_store(mine + ((i * TB + j) * 16 + r) * 64 + lane, acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      unsigned old = atomicAdd(&p.split_counters[q], 1u);
+      split_last = old == (unsigned)p.ksplit - 1 ? 1u : 0u;
+      if (split_last) p.split_counters[q] = 0;  // ready for the next launch
+    }
+    __syncthreads();
+    if (!split_last) return;
+    const float *tile_ws = p.split_ws + ((size_t)q * p.ksplit * (WF * WT) + wave) * (FB * TB * 16 * 64);
+    const size_t slice_stride = (size_t)(WF * WT) * (FB * TB * 16 * 64);
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      if (tb0 + wt * TB + j >= p.tok_blocks) continue;
+#pragma unroll
+      for (int i = 0; i < FB; ++i) {
+        f32x16_t sum;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[r] = 0.f;
+        for (int s0 = 0; s0 < p.ksplit; s0 += 4) {  // 4 slices x 16 values in flight
+          float v[4][16];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              v[u][r] = s0 + u < p.ksplit ? tile_ws[(size_t)(s0 + u) * slice_stride + ((i * TB + j) * 16 + r) * 64 + lane] : 0.f;
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum[r] += v[u][r];
+        }
+        acc[i][j] = sum;
+      }
+    }
+  }
 
   // ------------------------------------------------------------------ epilogue
   const int hh = lane >> 5, tl = lane & 31;
@@ -456,6 +515,12 @@ hipError_t mfma_rstd(const float *ssq_part, float *rstd, int rows, int H, float 
   return hipGetLastError();
 }
 
+constexpr int kGemmSplitCus = 256;    // workgroups that run at once (one per CU)
+constexpr int kGemmSplitUnits = 512;  // most (tile, slice) pairs of a split GEMM
+
+// largest scratch a split GEMM can use: kGemmSplitUnits partial tiles of 256 x 256 fp32
+size_t mfma_gemm_split_ws_bytes() { return (size_t)kGemmSplitUnits * (WF * WT) * (FB * TB * 16 * 64) * sizeof(float); }
+
 hipError_t mfma_gemm_init() {
   hipError_t e = hipFuncSetAttribute((const void *)k_gemm<EPI_STORE>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
@@ -476,7 +541,28 @@ hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N,
   p.Kc = ep.Kc; p.Vc = ep.Vc; p.geom = ep.geom; p.qd = ep.qd; p.kvd = ep.kvd;
   p.cos_tab = ep.cos_tab; p.sin_tab = ep.sin_tab; p.row_pos = ep.row_pos; p.row_req = ep.row_req;
   p.rstd = ep.rstd; p.xres = ep.xres; p.gain = ep.gain; p.row_ext = ep.row_ext; p.ssq_part = ep.ssq_part;
-  int grid = (p.n_tiles + 7) / 8 * 8;
+  p.tiles_grid = (p.n_tiles + 7) / 8 * 8;
+  // Few output tiles (short prompts): split the K loop over c workgroups per tile when a simple
+  // model says it pays.  Rounds of 256 workgroups times the share of a tile's K loop each one
+  // runs, against what the slices then write and read back (the token blocks that exist, fp32,
+  // at the ~3 TB/s write-through stores and the gather reach) plus the extra round trips.
+  // Slices are whole numbers of stages, at least 2 NST of them each.
+  p.ksplit = 1;
+  if (ep.split_ws && ep.split_counters && p.n_tiles <= kGemmSplitMaxTiles) {
+    const int nsteps = p.KT / KTS;
+    const double tile_us = K * 0.0267;  // 256 x 256 x K on one CU at the rate the big GEMMs run at
+    const int live_blocks = p.tok_blocks < XB ? p.tok_blocks : XB;
+    double best = 0.9 * (double)((p.n_tiles + kGemmSplitCus - 1) / kGemmSplitCus) * tile_us;  // a split has to win clearly
+    for (int c = 2; c <= 32 && p.n_tiles * c <= kGemmSplitUnits; ++c) {
+      if (nsteps % c != 0 || nsteps / c < 2 * NST) continue;
+      double rounds = (double)((p.n_tiles * c + kGemmSplitCus - 1) / kGemmSplitCus);
+      double partial_mb = (double)p.n_tiles * c * live_blocks * NBK * 4096.0 * 2 / 1e6;
+      double t = rounds * tile_us / c + partial_mb / 3.0 + 5.0;
+      if (t < best) { best = t; p.ksplit = c; }
+    }
+  }
+  p.split_ws = ep.split_ws; p.split_counters = ep.split_counters;
+  int grid = p.tiles_grid * p.ksplit;
   if (epi == EPI_STORE) k_gemm<EPI_STORE><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
   else if (epi == EPI_SWIGLU) k_gemm<EPI_SWIGLU><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
   else if (epi == EPI_RESID) k_gemm<EPI_RESID><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);

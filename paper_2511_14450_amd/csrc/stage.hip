@@ -35,7 +35,7 @@ struct Layout {
   size_t tok_req = 0, tok_pos = 0, lens = 0, iota = 0;
   // MFMA path only
   size_t q = 0, delta = 0, row_ext = 0, row_pos = 0, row_req = 0, tiles = 0, req_len = 0, row_ext_dec = 0, qdec = 0,
-         partial = 0, attn_part = 0, counters = 0, ssq = 0, rstd = 0, ssq_part = 0;
+         partial = 0, attn_part = 0, counters = 0, gemm_counters = 0, ssq = 0, rstd = 0, ssq_part = 0, gemm_ws = 0;
   size_t kv_bytes = 0;  // bytes of each of Kc, Vc over all layers
   int rows_cap = 0;     // internal rows the scratch holds
   int key_blocks = 0;   // 32-key blocks per (request, kv head)
@@ -144,7 +144,9 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.max_chunks = (c.max_seq + L.chunk_keys - 1) / L.chunk_keys;
     L.attn_part = take(sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks));
     L.counters = take(sizeof(unsigned) * (2 * I / 64 + (qd + 2 * kvd) / 64 + H / 64));
+    L.gemm_counters = take(sizeof(unsigned) * kGemmSplitMaxTiles);  // zeroed together with `counters`
     L.ssq = take(sizeof(float) * 32 * (H / 64));
+    L.gemm_ws = take(mfma_gemm_split_ws_bytes());
     L.total = off;
     return;
   }
@@ -326,10 +328,12 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
   float *rstd = at<float>(st, L.rstd), *ssq_part = at<float>(st, L.ssq_part);
   PROF(st, HYP_K_ADD_NORM, mfma_prefill_begin((const bf16_t *)hidden_in, xres, at<bf16_t>(st, L.layers[0].g1), y, rstd,
                                                row_ext, rows, d.H, d.eps, s));
+  GemmEpilogue split;  // scratch of GEMMs that split their K loop (short prompts leave few output tiles)
+  split.split_ws = at<float>(st, L.gemm_ws); split.split_counters = at<unsigned>(st, L.gemm_counters);
   for (int l = 0; l < st->n_layers; ++l) {
     const LayerPtrs &p = L.layers[l];
     const bool last = l + 1 == st->n_layers;
-    GemmEpilogue e;
+    GemmEpilogue e = split;
     e.Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l);
     e.Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
     e.geom = geom; e.qd = d.qd; e.kvd = d.kvd;
@@ -340,12 +344,12 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
     PROF(st, HYP_K_ATTN_PREFILL, mfma_attn_prefill(q, e.Kc, e.Vc, geom, attn, at<PrefillTile>(st, L.tiles), n_tiles,
                                   at<int>(st, L.req_len), d.nq, d.nkv, s));
     // residual add, the next norm's gain and its statistics all happen in the epilogue
-    GemmEpilogue r;
+    GemmEpilogue r = split;
     r.xres = xres; r.row_ext = row_ext; r.ssq_part = ssq_part;
     r.gain = at<bf16_t>(st, p.g2);
     PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_RESID, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, y, d.H, r, s));
     PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, rows, d.H, d.eps, s));
-    GemmEpilogue g;
+    GemmEpilogue g = split;
     g.rstd = rstd;
     PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, g, s));
     if (!last) {
@@ -353,7 +357,7 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
       PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_RESID, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, y, d.H, r, s));
       PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, rows, d.H, d.eps, s));
     } else {
-      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, GemmEpilogue(), s));
+      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, split, s));
       PROF(st, HYP_K_ADD_NORM, mfma_prefill_end(xres, delta, (bf16_t *)hidden_out, row_ext, rows, d.H, s));
     }
   }

@@ -70,6 +70,13 @@ def test_c2_layer_4x512_sampled_rows(phi3_layer):
     check_requests(phi3_layer, [512] * 4, 9100, sample_reqs=[0, 3], decode_steps=0)
 
 
+def test_short_prompts_full_width_split_k_gemms(phi3_layer):
+    # the paper's own request shape (Sec. V-A: 64-token prompts): one token tile, so the four
+    # GEMMs have 20 - 140 output tiles and split their K loop across workgroups
+    check_requests(phi3_layer, [64], 9150, sample_reqs=[0], decode_steps=1)
+    check_requests(phi3_layer, [64, 17, 1], 9160, sample_reqs=[0, 1, 2], decode_steps=1)
+
+
 def test_c3_layer_8x2048_sampled_rows_then_decode(phi3_layer):
     check_requests(phi3_layer, [2048] * 8, 9200, sample_reqs=[0, 5], decode_steps=2)
 

@@ -248,6 +248,11 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
     for (int i = 0; i < TB; ++i) xfr[which][i] = *(const bf16x8_t *)(base + ((wt * TB + i) * KTS + kt) * 1024);
   };
+  auto readfr1 = [&](int which, int buf, int kt, int m) {  // fragment m of FB + TB: one read in the shadow of one MFMA
+    const char *base = lds + buf * STAGE_BYTES + lane * 16;
+    if (m < FB) wfr[which][m] = *(const bf16x8_t *)(base + ((XB + wf * FB + m) * KTS + kt) * 1024);
+    else xfr[which][m - FB] = *(const bf16x8_t *)(base + ((wt * TB + (m - FB)) * KTS + kt) * 1024);
+  };
   readfr(0, 0, 0);
   int buf = 0;
   for (int s = 0; s + 1 < nsteps; ++s) {
@@ -268,9 +273,9 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
           for (int j = 0; j < TB; ++j) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
-            if (i == 0 && j == 0) {
+            if (i * TB + j < FB + TB) {
               __builtin_amdgcn_sched_barrier(0);
-              readfr(n, nbuf, 0);
+              readfr1(n, nbuf, 0, i * TB + j);
               __builtin_amdgcn_sched_barrier(0);
             }
             if (((i * TB + j) & 1) == 1 && ((i * TB + j) >> 1) < LPW) issue1((i * TB + j) >> 1, lstep, buf);
@@ -283,9 +288,9 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
           for (int j = 0; j < TB; ++j) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
-            if (i == 0 && j == 0) {
+            if (i * TB + j < FB + TB) {
               __builtin_amdgcn_sched_barrier(0);
-              readfr(n, buf, kt + 1);
+              readfr1(n, buf, kt + 1, i * TB + j);
               __builtin_amdgcn_sched_barrier(0);
             }
           }

@@ -278,7 +278,10 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
               readfr1(n, nbuf, 0, i * TB + j);
               __builtin_amdgcn_sched_barrier(0);
             }
-            if (((i * TB + j) & 1) == 1 && ((i * TB + j) >> 1) < LPW) issue1((i * TB + j) >> 1, lstep, buf);
+            if (((i * TB + j) & 1) == 1 && ((i * TB + j) >> 1) < LPW) {
+              issue1((i * TB + j) >> 1, lstep, buf);
+              __builtin_amdgcn_sched_barrier(0);
+            }
           }
       } else {
         __builtin_amdgcn_s_setprio(1);

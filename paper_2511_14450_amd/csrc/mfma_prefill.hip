@@ -137,9 +137,12 @@ __global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part
 // tokens), each wave 2 x 4 accumulator blocks of 32x32 (128 fp32 registers).
 // K advances in stages of 32 (2 k-tiles); 4 stages of 32 KiB rotate through LDS
 // and are filled by direct global->LDS wave loads issued three stages ahead, 4
-// per wave and stage, interleaved with the MFMAs.  Fragments are read from LDS
-// with linear, conflict-free ds_read_b128 one k-tile ahead of the MFMAs that
-// use them.  One barrier per stage.  Workgroups are numbered so that the ones
+// per wave and stage.  Fragments are read from LDS with linear, conflict-free
+// ds_read_b128 one k-tile ahead of the MFMAs that use them.  Every LDS read and
+// every global->LDS load is pinned behind one particular MFMA of the k-tile (reads
+// after the first six, loads after every second one): left to the compiler they
+// bunch up and the matrix pipe waits for the burst to issue.
+// One barrier per stage.  Workgroups are numbered so that the ones
 // that run together on an XCD (id % 8) cover a band of `gm` token tiles times
 // consecutive feature tiles and share operand panels in that XCD's L2.
 // ----------------------------------------------------------------------------
@@ -191,7 +194,7 @@ __device__ __forceinline__ void store_block(bf16_t *out, int out_K, int tb, int 
 template <int EPI>
 __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // wave-uniform: scalar registers
   const int wf = wave / WT, wt = wave % WT;
   // tile of this workgroup
   __shared__ unsigned split_last;
@@ -266,7 +269,6 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0x0070 | (((NST - 2) * LPW) & 15) | ((((NST - 2) * LPW) >> 4) << 14));
         __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_s_setprio(1);  // MFMA clusters win issue arbitration over the other wave's loads
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < FB; ++i)
@@ -278,13 +280,12 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
               readfr1(n, nbuf, 0, i * TB + j);
               __builtin_amdgcn_sched_barrier(0);
             }
-            if (((i * TB + j) & 1) == 1 && ((i * TB + j) >> 1) < LPW) {
+            if (((i * TB + j) & 1) == 0 && ((i * TB + j) >> 1) < LPW) {
               issue1((i * TB + j) >> 1, lstep, buf);
               __builtin_amdgcn_sched_barrier(0);
             }
           }
       } else {
-        __builtin_amdgcn_s_setprio(1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < FB; ++i)
@@ -299,7 +300,6 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
           }
       }
     }
-    __builtin_amdgcn_s_setprio(0);
     buf = nbuf;
   }
 #pragma unroll

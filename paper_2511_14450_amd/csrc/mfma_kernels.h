@@ -100,12 +100,15 @@ hipError_t mfma_attn_decode(const bf16_t *qdec, const bf16_t *Kc, const bf16_t *
                             const int *lens, float *part, bf16_t *out, int nq, int nkv, int batch,
                             int max_chunks, int chunk_keys, hipStream_t s);
 size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks);
-// keys per decode-attention chunk (one wave each): 128, or 256 when that still leaves
-// too few waves to matter (measured: 8 x 10 heads x 2K context runs 11 % faster with
-// 256, 32 x 10 x 4K 6 % slower), doubled until a context has at most 64 chunks
+// keys per decode-attention chunk (one wave each, one wave per SIMD): the largest power-of-two
+// multiple of 128 up to 1024 that still gives the longest context about 512 waves over all
+// (request, KV head) pairs - chunks of 256 for 8 x 10 pairs at 2K keys, 1024 for 32 x 10
+// pairs at 1K - 4K and for 8 x 10 pairs at 9K (measured over 128 .. 1408 keys per chunk:
+// fewer, longer waves beat more rounds of short ones until a wave's own serial time shows),
+// doubled until a context has at most 64 chunks
 inline int mfma_decode_chunk_keys(int max_seq, int heads_in_flight) {
-  int c = 128;
-  if ((long)heads_in_flight * ((max_seq + c - 1) / c) < 2048) c = 256;
+  int c = 1024;
+  while (c > 128 && (long)heads_in_flight * ((max_seq + c - 1) / c) < 512) c /= 2;
   while ((max_seq + c - 1) / c > 64) c *= 2;
   return c;
 }

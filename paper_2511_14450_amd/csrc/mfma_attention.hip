@@ -324,9 +324,17 @@ __global__ void __launch_bounds__(128) k_attn_decode_merge(const float *__restri
   const int n_chunks = (lens[req] + 1 + chunk_keys - 1) / chunk_keys;  // <= 64 by the host's choice of chunk_keys
   const float c = kLog2e * 0.08838834764831845f;
   const float *src = part + ((size_t)req * nq + head) * max_chunks * kPartStride;
+  // One round trip: the first 16 chunks' outputs, the maxima and the sums are requested for every
+  // chunk slot the buffer has, without waiting for the request's length; slots past n_chunks hold
+  // whatever an earlier step left there and are dropped below without entering any arithmetic.
+  float v0[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) v0[u] = u < max_chunks ? src[u * kPartStride + 2 + d] : 0.f;
+  float mi_raw = 0.f, li_raw = 0.f;
+  if (d < 64 && d < max_chunks) { mi_raw = src[d * kPartStride]; li_raw = src[d * kPartStride + 1]; }
   if (d < 64) {
-    float mi = d < n_chunks ? src[d * kPartStride] : -INFINITY;
-    float li = d < n_chunks ? src[d * kPartStride + 1] : 0.f;
+    float mi = d < n_chunks ? mi_raw : -INFINITY;
+    float li = d < n_chunks ? li_raw : 0.f;
     float m = mi;
     for (int o2 = 32; o2 > 0; o2 >>= 1) m = fmaxf(m, __shfl_xor(m, o2, 64));
     float w = d < n_chunks ? exp2f((mi - m) * c) : 0.f;
@@ -337,7 +345,10 @@ __global__ void __launch_bounds__(128) k_attn_decode_merge(const float *__restri
   }
   __syncthreads();
   float acc = 0.f;
-  int i = 0;
+#pragma unroll
+  for (int u = 0; u < 16; ++u)
+    if (u < n_chunks) acc += wgt[u] * v0[u];
+  int i = 16;
   for (; i + 8 <= n_chunks; i += 8) {
     float v[8];
 #pragma unroll

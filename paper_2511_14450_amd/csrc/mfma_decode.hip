@@ -20,7 +20,8 @@ namespace {
 // with fully coalesced 1 KiB loads straight into registers.  x = P(32, K) is
 // tiny and stays in L2.  A workgroup owns 64 packed rows (2 blocks); its 4 waves
 // split the workgroup's K slice and are reduced through LDS in wave order; the
-// `ksplit` workgroups of one row group write fp32 partial sums, and the one that
+// `ksplit` workgroups of one row group (twice as many for the row groups that would
+// otherwise form a thin second round of the launch) write fp32 partial sums, and the one that
 // arrives last (a counter per row group) adds them up in slice order - so the
 // result does not depend on which one that is - and runs the epilogue.  The
 // partial sums are written with device-scope (write-through) stores that have
@@ -49,6 +50,8 @@ struct DecGemvParams {
   float *partial;
   unsigned *counters;
   int N, KT, ksplit, tiles_per_wave, batch;
+  // row groups from `groups1` on are split twice as fine (they run last and keep the launch's tail short)
+  int groups1, n_groups;
   const float *ssq_in;  // [n_ssq][32]
   int n_ssq;
   float inv_H, eps;
@@ -77,7 +80,18 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
   __shared__ unsigned is_last;
   float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1]) & red[0][0][0];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int fb0 = blockIdx.x * FBW, ks = blockIdx.y;
+  // 1-D grid: first the `ksplit` slices of row groups [0, groups1), slice-major, then the
+  // 2 * ksplit slices of the remaining groups
+  int group, ks, ksplit = p.ksplit, tiles_per_wave = p.tiles_per_wave;
+  {
+    const int first = p.groups1 * p.ksplit, id = blockIdx.x;
+    if (id < first) { group = id % p.groups1; ks = id / p.groups1; }
+    else {
+      const int g2 = p.n_groups - p.groups1, id2 = id - first;
+      group = p.groups1 + id2 % g2; ks = id2 / g2; ksplit *= 2; tiles_per_wave >>= 1;
+    }
+  }
+  const int fb0 = group * FBW;
   // positions of the step's tokens (the QKV epilogue's rotary angles depend on them): fetched under the streaming loop
   // (ahead of time for the first kPf * 8 tokens, which covers the usual batch; the rest is loaded in place)
   constexpr int kPf = 2;
@@ -92,7 +106,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
   // the workgroup's four waves take the k-tiles of its slice in turn, so that each step of
   // the workgroup reads 4 KiB contiguous per row block (HBM serves that pattern ~10 % faster
   // than four separate 1 KiB streams)
-  const int kt0 = ks * NW * p.tiles_per_wave + wave;
+  const int kt0 = ks * NW * tiles_per_wave + wave;
   constexpr size_t kStep = (size_t)NW * kTileElems;
   f32x16_t acc[FBW];
 #pragma unroll
@@ -118,7 +132,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
 #pragma unroll
     for (int i = 0; i < FBW; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i][u], xf[u], acc[i], 0, 0, 0);
   };
-  const int n_win = p.tiles_per_wave / UNROLL, rem = p.tiles_per_wave - n_win * UNROLL;
+  const int n_win = tiles_per_wave / UNROLL, rem = tiles_per_wave - n_win * UNROLL;
   if (n_win > 0) {
     int t = 0;
 #pragma unroll
@@ -176,18 +190,18 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     int idx = threadIdx.x + j * NW * 64;
     if (idx < n_pairs) {
       int f = idx % kGroupRows, token = idx / kGroupRows;
-      if (p.ksplit > 1)  // write-through store: visible to the other XCDs once it has completed
+      if (ksplit > 1)  // write-through store: visible to the other XCDs once it has completed
         __hip_atomic_store(&p.partial[((size_t)ks * 32 + token) * p.N + fb0 * 32 + f], mine[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       else fin[token][f] = mine[j];
     }
   }
-  if (p.ksplit > 1) {
+  if (ksplit > 1) {
     __builtin_amdgcn_s_waitcnt(0);  // this thread's partial sums have completed ...
     __syncthreads();
     if (threadIdx.x == 0) {  // ... before it is counted
-      unsigned old = atomicAdd(&p.counters[blockIdx.x], 1u);
-      is_last = (old == (unsigned)p.ksplit - 1) ? 1u : 0u;
-      if (is_last) p.counters[blockIdx.x] = 0;  // ready for the next launch
+      unsigned old = atomicAdd(&p.counters[group], 1u);
+      is_last = (old == (unsigned)ksplit - 1) ? 1u : 0u;
+      if (is_last) p.counters[group] = 0;  // ready for the next launch
     }
     __syncthreads();
     if (!is_last) return;
@@ -232,7 +246,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
       ssq_v[u] = g < p.n_ssq ? p.ssq_in[g * 32 + ssq_tkn] : 0.f;
     }
   }
-  if (p.ksplit > 1) {
+  if (ksplit > 1) {
     // Plain loads are enough here: every 256-byte run of `partial` has exactly one
     // writer in this launch, this XCD's L2 was invalidated when the launch began,
     // and nothing in this launch read these lines before, so a line is either
@@ -241,7 +255,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     // pairs per thread and GW slices of each are in flight at once; slices beyond ksplit are masked
     // rather than peeled, so the gather costs ceil(ksplit / GW) round trips.
     constexpr int GW = EPI == DEC_QKV ? 8 : 16;
-    if (p.ksplit <= 4) {
+    if (ksplit <= 4) {
       // few slices: four of the thread's pairs at once (16 tokens' worth per round trip)
       for (int j0 = 0; j0 * NW * 64 < n_pairs; j0 += 4) {
         float v[4][4];
@@ -251,7 +265,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
           const bool has = idx < n_pairs;
           const unsigned off = has ? (unsigned)((idx / kGroupRows) * p.N + fb0 * 32 + idx % kGroupRows) : 0u;
 #pragma unroll
-          for (int u = 0; u < 4; ++u) v[j][u] = has && u < p.ksplit ? (p.partial + (size_t)u * 32 * p.N)[off] : 0.f;
+          for (int u = 0; u < 4; ++u) v[j][u] = has && u < ksplit ? (p.partial + (size_t)u * 32 * p.N)[off] : 0.f;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -267,11 +281,11 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
         const unsigned off0 = (unsigned)((idx0 / kGroupRows) * p.N + fb0 * 32 + idx0 % kGroupRows);
         const unsigned off1 = (unsigned)(((has1 ? idx1 : idx0) / kGroupRows) * p.N + fb0 * 32 + (has1 ? idx1 : idx0) % kGroupRows);
         float sum0 = 0.f, sum1 = 0.f;
-        for (int s = 0; s < p.ksplit; s += GW) {
+        for (int s = 0; s < ksplit; s += GW) {
           float v0[GW], v1[GW];
 #pragma unroll
           for (int u = 0; u < GW; ++u) {
-            const bool in = s + u < p.ksplit;
+            const bool in = s + u < ksplit;
             const float *slice = p.partial + (size_t)(s + u) * 32 * p.N;
             v0[u] = in ? slice[off0] : 0.f;
             v1[u] = in && has1 ? slice[off1] : 0.f;
@@ -360,13 +374,13 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
         p.hidden_out[(size_t)b * p.H + n0 + f] = f2bf_dev(xn);
       }
     }
-    if (EPI == DEC_FINAL && blockIdx.x == 0 && p.lens_advance && threadIdx.x < p.batch) p.lens_advance[threadIdx.x] += 1;
+    if (EPI == DEC_FINAL && group == 0 && p.lens_advance && threadIdx.x < p.batch) p.lens_advance[threadIdx.x] += 1;
     if (EPI == DEC_RESID) {
       __syncthreads();
       if (threadIdx.x < p.batch) {
         float ss = 0.f;
         for (int f = 0; f < kGroupRows; ++f) ss += fin[threadIdx.x][f];
-        p.ssq_out[blockIdx.x * 32 + threadIdx.x] = ss;
+        p.ssq_out[group * 32 + threadIdx.x] = ss;
       }
     }
   }
@@ -447,7 +461,15 @@ hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s) {
   p.lens = a.lens; p.cos_tab = a.cos_tab; p.sin_tab = a.sin_tab; p.qdec = a.qdec; p.Kc = a.Kc; p.Vc = a.Vc;
   p.geom = a.geom; p.nq = a.nq; p.nkv = a.nkv; p.m_out = a.m_out; p.I = a.I; p.xres = a.xres; p.gain = a.gain;
   p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H; p.lens_advance = a.lens_advance;
-  dim3 grid(a.N / kGroupRows, a.ksplit);
+  // When the slices of all row groups do not fit the chip at once (4 workgroups per CU) but
+  // would in fewer than two rounds, the groups beyond the first round get twice the slices:
+  // twice as many waves, half as long, for what would otherwise be a thin second round.
+  const int groups = a.N / kGroupRows, slots = 4 * 256;
+  p.n_groups = groups; p.groups1 = groups;
+  if (a.ksplit >= 1 && groups * a.ksplit > slots && groups * a.ksplit < 2 * slots && p.tiles_per_wave % 2 == 0 &&
+      p.tiles_per_wave / 2 >= UNROLL && 2 * a.ksplit <= a.max_ksplit)
+    p.groups1 = slots / a.ksplit;
+  dim3 grid(p.groups1 * a.ksplit + (groups - p.groups1) * 2 * a.ksplit);
   switch (epi) {
     case DEC_QKV: k_dec_gemv<DEC_QKV><<<grid, NW * 64, 0, s>>>(p); break;
     case DEC_SWIGLU: k_dec_gemv<DEC_SWIGLU><<<grid, NW * 64, 0, s>>>(p); break;

@@ -68,9 +68,10 @@ enum { DEC_QKV = 0, DEC_SWIGLU = 1, DEC_RESID = 2, DEC_FINAL = 3 };
 // stay null / 0.
 struct DecGemv {
   const bf16_t *W = nullptr, *x = nullptr;  // P(N, K), P(32, K)
-  float *partial = nullptr;                 // [ksplit][32][N]
+  float *partial = nullptr;                 // [max_ksplit][32][N]
   unsigned *counters = nullptr;             // [N / 64], zero between launches
   int N = 0, K = 0, ksplit = 1, batch = 0;
+  int max_ksplit = 1;                       // slices `partial` has room for (the launcher may split some row groups finer)
   const float *ssq_in = nullptr;            // [n_ssq][32] sums of squares of the normalised input
   int n_ssq = 0;
   float eps = 0.f;

@@ -139,7 +139,7 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.ks_d = mfma_gemv_ksplit((int)H, (int)I, c.max_batch);
     size_t pf = std::max(std::max((size_t)L.ks_qkv * (qd + 2 * kvd), (size_t)L.ks_o * H),
                          std::max((size_t)L.ks_gu * 2 * I, (size_t)L.ks_d * H));
-    L.partial = take(sizeof(float) * pf * 32);
+    L.partial = take(sizeof(float) * pf * 32 * 2);  // room for twice the slices (row groups split finer at the end of a launch)
     L.chunk_keys = mfma_decode_chunk_keys(c.max_seq, c.max_batch * c.n_kv_heads);
     L.max_chunks = (c.max_seq + L.chunk_keys - 1) / L.chunk_keys;
     L.attn_part = take(sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks));
@@ -388,7 +388,7 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const void *hidden_i
     const LayerPtrs &p = L.layers[l];
     bf16_t *Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l), *Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
     DecGemv a = base;
-    a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.ksplit = L.ks_qkv;
+    a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.ksplit = L.ks_qkv; a.max_ksplit = 2 * a.ksplit;
     a.ssq_in = ssq; a.n_ssq = d.H / 64;
     a.lens = at<int>(st, L.lens); a.cos_tab = at<float>(st, L.cos_tab); a.sin_tab = at<float>(st, L.sin_tab);
     a.qdec = at<bf16_t>(st, L.qdec); a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
@@ -397,15 +397,15 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const void *hidden_i
                                                  attn, d.nq, d.nkv, st->batch,
                                                  L.max_chunks, L.chunk_keys, s));
     DecGemv o = base;
-    o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.ksplit = L.ks_o;
+    o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.ksplit = L.ks_o; o.max_ksplit = 2 * o.ksplit;
     o.gain = at<bf16_t>(st, p.g2); o.y_out = y; o.ssq_out = ssq;
     PROF(st, HYP_K_GEMV_O, mfma_dec_gemv(DEC_RESID, o, s));
     DecGemv g = base;
-    g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.ksplit = L.ks_gu;
+    g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.ksplit = L.ks_gu; g.max_ksplit = 2 * g.ksplit;
     g.ssq_in = ssq; g.n_ssq = d.H / 64; g.m_out = m; g.I = d.I;
     PROF(st, HYP_K_GEMV_GATEUP, mfma_dec_gemv(DEC_SWIGLU, g, s));
     DecGemv w = base;
-    w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.ksplit = L.ks_d;
+    w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.ksplit = L.ks_d; w.max_ksplit = 2 * w.ksplit;
     if (l + 1 < st->n_layers) {
       w.gain = at<bf16_t>(st, L.layers[l + 1].g1); w.y_out = y; w.ssq_out = ssq;
       PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_RESID, w, s));

@@ -40,10 +40,9 @@ namespace {
 // ----------------------------------------------------------------------------
 // UNROLL k-tiles per batch: 10 weight loads of 1 KiB in flight per wave and 4 workgroups per
 // CU (124 registers) measured better than 20 in flight at 3 per CU
-constexpr int FBW = 2, NW = 4, UNROLL = 5;
-constexpr int kGroupRows = FBW * 32;
+constexpr int NW = 4;
 constexpr int kSsqParts = NW * 2;  // interleaved partial sums of the row groups' sums of squares (one per 32 threads)
-constexpr int kRedStride = kGroupRows + 4;  // keeps 16-byte alignment, spreads tokens over banks
+constexpr int kBeginRows = 64;  // rows per workgroup of the kernel that opens a step (and per sum of squares it writes)
 
 struct DecGemvParams {
   const bf16_t *W, *x;
@@ -71,8 +70,15 @@ struct DecGemvParams {
   int *lens_advance;  // DEC_FINAL: cached lengths to bump once the step's last kernel finishes
 };
 
-template <int EPI>
+// FBW row blocks of 32 per workgroup: 2 where an epilogue pairs rows of two blocks (RoPE partners,
+// gate and up) and for long K; 1 for the residual epilogues at short K, where 32-row workgroups with
+// a 10-tile window give as many waves with as much in flight as two slices of 64-row workgroups
+// would, without partial sums, counter and gather at the end.
+template <int EPI, int FBW>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) k_dec_gemv(DecGemvParams p) {
+  constexpr int UNROLL = FBW == 1 ? 10 : 5;
+  constexpr int kGroupRows = FBW * 32;
+  constexpr int kRedStride = kGroupRows + 4;  // keeps 16-byte alignment, spreads tokens over banks
   // the waves' sums as [wave][token][row]: rows contiguous so that the cross-wave add reads
   // without bank conflicts; 34 KiB, reused as fin[32][65] once reduced
   __shared__ __attribute__((aligned(16))) float red[NW][32][kRedStride];
@@ -391,10 +397,10 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
 __global__ void __launch_bounds__(256) k_dec_begin(const bf16_t *__restrict__ hidden_in, float *__restrict__ xres,
                                                    const bf16_t *__restrict__ gain, bf16_t *__restrict__ y_out,
                                                    float *__restrict__ ssq_out, int H, int batch) {
-  __shared__ float sq[32][kGroupRows + 1];
-  const int n0 = blockIdx.x * kGroupRows;
-  for (int idx = threadIdx.x; idx < batch * kGroupRows; idx += 256) {
-    int f = idx % kGroupRows, b = idx / kGroupRows;
+  __shared__ float sq[32][kBeginRows + 1];
+  const int n0 = blockIdx.x * kBeginRows;
+  for (int idx = threadIdx.x; idx < batch * kBeginRows; idx += 256) {
+    int f = idx % kBeginRows, b = idx / kBeginRows;
     float x = bf16_to_f32(hidden_in[(size_t)b * H + n0 + f]);
     xres[(size_t)b * H + n0 + f] = x;
     y_out[frag_offset(b, n0 + f, H)] = f2bf_dev(x * bf16_to_f32(gain[n0 + f]));
@@ -403,7 +409,7 @@ __global__ void __launch_bounds__(256) k_dec_begin(const bf16_t *__restrict__ hi
   __syncthreads();
   if (threadIdx.x < batch) {
     float ss = 0.f;
-    for (int f = 0; f < kGroupRows; ++f) ss += sq[threadIdx.x][f];
+    for (int f = 0; f < kBeginRows; ++f) ss += sq[threadIdx.x][f];
     ssq_out[blockIdx.x * 32 + threadIdx.x] = ss;
   }
 }
@@ -453,35 +459,46 @@ int mfma_gemv_ksplit(int N, int K, int batch) {
   return best;
 }
 
+// Residual GEMMs whose K fits one slice of at most 112 k-tiles per wave run as 32-row workgroups
+// without any split (same number of waves, same bytes in flight, no partial sums)
+int mfma_gemv_resid_fbw(int K) { return K / 16 / NW <= 112 && (K / 16) % NW == 0 ? 1 : 2; }
+
 hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s) {
   DecGemvParams p = {};
   p.W = a.W; p.x = a.x; p.partial = a.partial; p.counters = a.counters;
   p.N = a.N; p.KT = a.K / 16; p.ksplit = a.ksplit; p.tiles_per_wave = p.KT / (a.ksplit * NW); p.batch = a.batch;
-  p.ssq_in = a.ssq_in; p.n_ssq = a.n_ssq; p.inv_H = a.n_ssq ? 1.0f / (float)(a.n_ssq * kGroupRows) : 0.f; p.eps = a.eps;
+  p.ssq_in = a.ssq_in; p.n_ssq = a.n_ssq; p.inv_H = a.n_ssq ? 1.0f / (float)a.K : 0.f; p.eps = a.eps;
   p.lens = a.lens; p.cos_tab = a.cos_tab; p.sin_tab = a.sin_tab; p.qdec = a.qdec; p.Kc = a.Kc; p.Vc = a.Vc;
   p.geom = a.geom; p.nq = a.nq; p.nkv = a.nkv; p.m_out = a.m_out; p.I = a.I; p.xres = a.xres; p.gain = a.gain;
   p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H; p.lens_advance = a.lens_advance;
   // When the slices of all row groups do not fit the chip at once (4 workgroups per CU) but
   // would in fewer than two rounds, the groups beyond the first round get twice the slices:
   // twice as many waves, half as long, for what would otherwise be a thin second round.
-  const int groups = a.N / kGroupRows, slots = 4 * 256;
+  const int fbw = (a.fbw == 1 && (epi == DEC_RESID || epi == DEC_FINAL)) ? 1 : 2;
+  const int groups = a.N / (fbw * 32), slots = 4 * 256;
   p.n_groups = groups; p.groups1 = groups;
-  if (a.ksplit >= 1 && groups * a.ksplit > slots && groups * a.ksplit < 2 * slots && p.tiles_per_wave % 2 == 0 &&
-      p.tiles_per_wave / 2 >= UNROLL && 2 * a.ksplit <= a.max_ksplit)
+  if (groups * a.ksplit > slots && groups * a.ksplit < 2 * slots && p.tiles_per_wave % 2 == 0 &&
+      p.tiles_per_wave / 2 >= 10 && 2 * a.ksplit <= a.max_ksplit)
     p.groups1 = slots / a.ksplit;
   dim3 grid(p.groups1 * a.ksplit + (groups - p.groups1) * 2 * a.ksplit);
   switch (epi) {
-    case DEC_QKV: k_dec_gemv<DEC_QKV><<<grid, NW * 64, 0, s>>>(p); break;
-    case DEC_SWIGLU: k_dec_gemv<DEC_SWIGLU><<<grid, NW * 64, 0, s>>>(p); break;
-    case DEC_RESID: k_dec_gemv<DEC_RESID><<<grid, NW * 64, 0, s>>>(p); break;
-    default: k_dec_gemv<DEC_FINAL><<<grid, NW * 64, 0, s>>>(p); break;
+    case DEC_QKV: k_dec_gemv<DEC_QKV, 2><<<grid, NW * 64, 0, s>>>(p); break;
+    case DEC_SWIGLU: k_dec_gemv<DEC_SWIGLU, 2><<<grid, NW * 64, 0, s>>>(p); break;
+    case DEC_RESID:
+      if (fbw == 1) k_dec_gemv<DEC_RESID, 1><<<grid, NW * 64, 0, s>>>(p);
+      else k_dec_gemv<DEC_RESID, 2><<<grid, NW * 64, 0, s>>>(p);
+      break;
+    default:
+      if (fbw == 1) k_dec_gemv<DEC_FINAL, 1><<<grid, NW * 64, 0, s>>>(p);
+      else k_dec_gemv<DEC_FINAL, 2><<<grid, NW * 64, 0, s>>>(p);
+      break;
   }
   return hipGetLastError();
 }
 
 hipError_t mfma_dec_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y_out, float *ssq_out,
                           int H, int batch, hipStream_t s) {
-  k_dec_begin<<<H / kGroupRows, 256, 0, s>>>(hidden_in, xres, gain, y_out, ssq_out, H, batch);
+  k_dec_begin<<<H / kBeginRows, 256, 0, s>>>(hidden_in, xres, gain, y_out, ssq_out, H, batch);
   return hipGetLastError();
 }
 

@@ -69,9 +69,11 @@ enum { DEC_QKV = 0, DEC_SWIGLU = 1, DEC_RESID = 2, DEC_FINAL = 3 };
 struct DecGemv {
   const bf16_t *W = nullptr, *x = nullptr;  // P(N, K), P(32, K)
   float *partial = nullptr;                 // [max_ksplit][32][N]
-  unsigned *counters = nullptr;             // [N / 64], zero between launches
+  unsigned *counters = nullptr;             // [N / 32], zero between launches
   int N = 0, K = 0, ksplit = 1, batch = 0;
   int max_ksplit = 1;                       // slices `partial` has room for (the launcher may split some row groups finer)
+  int fbw = 2;                              // DEC_RESID / DEC_FINAL: 32-row blocks per workgroup (1 or 2); sets the
+                                            // granularity of ssq_out (sums of squares per 32 or 64 rows)
   const float *ssq_in = nullptr;            // [n_ssq][32] sums of squares of the normalised input
   int n_ssq = 0;
   float eps = 0.f;
@@ -92,6 +94,7 @@ struct DecGemv {
 };
 hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s);
 int mfma_gemv_ksplit(int N, int K, int batch);
+int mfma_gemv_resid_fbw(int K);  // 1: run the residual GEMM of this K as unsplit 32-row workgroups
 // x = hidden_in ; xres = x ; y' = x * gain -> P(32, H) ; ssq_out[H/64][32]
 hipError_t mfma_dec_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y_out, float *ssq_out,
                           int H, int batch, hipStream_t s);

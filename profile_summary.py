@@ -25,7 +25,10 @@ CLASS_OF = [  # (regex on the kernel name, grid-x test, class)
     # down projection (last block of the stage) the only plain-epilogue one
     (r"k_gemm<3>", "gemm_o"), (r"k_gemm<0>", "gemm_down"), (r"k_rstd", "add_norm"),
     (r"k_attn_decode_merge", "attn_decode_merge"), (r"k_attn_decode", "attn_decode"),
-    (r"k_dec_gemv<0>", "gemv_qkv"), (r"k_dec_gemv<1>", "gemv_gateup"), (r"k_add_norm", "add_norm"),
+    (r"k_dec_gemv<0, \d>", "gemv_qkv"), (r"k_dec_gemv<1, \d>", "gemv_gateup"), (r"k_add_norm", "add_norm"),
+    # residual decode GEMMs: 32-row workgroups are the O projection, 64-row ones the down projection
+    # (on the bench shapes; the grid table below covers a build where both use 64 rows)
+    (r"k_dec_gemv<2, 1>", "gemv_o"), (r"k_dec_gemv<3, 1>", "gemv_o"),
     (r"k_dec_begin", "dec_begin"),
 ]
 
@@ -33,8 +36,8 @@ CLASS_OF = [  # (regex on the kernel name, grid-x test, class)
 # kernels shared by two classes, told apart by their launch size on the c3 workload
 # (total work-items): the decode O / down projections differ in ksplit
 NAME_BY_GRID = {
-    "k_dec_gemv<2>/grid40960": "gemv_o", "k_dec_gemv<3>/grid102400": "gemv_down",
-    "k_dec_gemv<2>/grid102400": "gemv_down",
+    "k_dec_gemv<2, 2>/grid102400": "gemv_down", "k_dec_gemv<3, 2>/grid102400": "gemv_down",
+    "k_dec_gemv<2, 2>/grid40960": "gemv_o",
 }
 
 
@@ -51,7 +54,7 @@ def classify(row) -> str:
     for pat, cls in CLASS_OF:
         if re.search(pat, n):
             return cls
-    if n.startswith("k_dec_gemv<2>") or n.startswith("k_dec_gemv<3>"):
+    if n.startswith("k_dec_gemv<2") or n.startswith("k_dec_gemv<3"):
         return n + f"/grid{grid}"
     return n
 

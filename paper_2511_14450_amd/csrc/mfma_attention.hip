@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
 // serves: S^T[key, head] = K q^T.  K and V fragments go straight from HBM into
 // registers (fragment order = operand order), 16 wave loads of 1 KiB per 32-key
 // block, no LDS.  One wave owns a chunk of chunk_keys keys of one
-// (request, KV head); chunks balance ragged contexts by tokens.  Every chunk
+// (request, KV head).  Every chunk
 // writes (max, sum, unnormalised output) and a second small kernel merges the
 // chunks of a head in index order, so the result does not depend on scheduling.
 // part layout: [request][head][chunk][130] = {m, l, o[128]}

@@ -29,7 +29,8 @@
  * All pointers are plain addresses.  "device" = memory of the current HIP device
  * that the caller owns (e.g. a PyTorch tensor's storage) and keeps alive for the
  * time stated; "host" = ordinary process memory.  No call allocates or frees
- * device memory: the caller supplies one workspace.  No call throws, aborts or
+ * device memory: the caller supplies one workspace.  No call throws (C++ exceptions
+ * are caught at the boundary and become HYP_ENOMEM / HYP_EDEVICE), aborts or
  * prints; every failure is a status code plus a message from stage_last_error().
  * A stage is not thread-safe; use one stage per host thread or lock outside.
  */
@@ -154,8 +155,9 @@ HYP_API hyp_status_t stage_export_kv(hyp_stage_t *stage, int32_t layer, int32_t 
 HYP_API hyp_status_t stage_context_len(const hyp_stage_t *stage, int32_t request, int32_t *len_out);
 
 /* Release host state.  The workspace returns to the caller, who must first
- * synchronise the stream.  stage_destroy(NULL) is HYP_EINVAL; destroying the
- * same pointer twice is undefined, like free(). */
+ * synchronise the stream.  stage_destroy(NULL) is HYP_EINVAL, and so is a pointer that
+ * is not a live handle of this library (e.g. a stage destroyed twice): every entry
+ * point checks its handle against the set of live stages before touching it. */
 HYP_API hyp_status_t stage_destroy(hyp_stage_t *stage);
 
 /* Message of the last failing call on this stage (or, with stage == NULL, of the

@@ -44,7 +44,7 @@ hipError_t mfma_prefill_begin(const bf16_t *hidden_in, float *xres, const bf16_t
 hipError_t mfma_prefill_end(const float *xres, const bf16_t *delta_bf, bf16_t *hidden_out, const int *row_ext,
                             int rows, int H, hipStream_t s);
 // rstd[row] from the per-group sums of squares of EPI_RESID
-hipError_t mfma_rstd(const float *ssq_part, float *rstd, int rows, int H, float eps, hipStream_t s);
+hipError_t mfma_rstd(const float *ssq_part, float *rstd, const int *row_ext, int rows, int H, float eps, hipStream_t s);
 
 hipError_t mfma_gemm_init();
 // out^T[N, rows] = W[N,K] X[rows,K]^T with the epilogue `epi`; rows % 32 == 0,

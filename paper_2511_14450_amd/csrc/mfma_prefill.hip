@@ -109,16 +109,17 @@ __global__ void __launch_bounds__(256) k_add_norm(const bf16_t *__restrict__ hid
   if (cg == 0) {
     float tot = 0.f;
     for (int i = 0; i < CPR; ++i) tot += red[r8][i];
-    rstd[row] = 1.0f / sqrtf(tot / (float)H + eps);
+    rstd[row] = ext < 0 ? 0.f : 1.0f / sqrtf(tot / (float)H + eps);  // padding rows stay zero also when eps == 0
   }
 }
 
 // rstd[row] = 1 / sqrt(mean square + eps) from the sums of squares the residual
 // epilogue left per 64-feature group: ssq_part[group][row], added in group order.
-__global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part, float *__restrict__ rstd, int rows,
-                                              int groups, float inv_H, float eps) {
+__global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part, float *__restrict__ rstd,
+                                              const int *__restrict__ row_ext, int rows, int groups, float inv_H, float eps) {
   int row = blockIdx.x * 256 + threadIdx.x;
   if (row >= rows) return;
+  const bool live = row_ext[row] >= 0;
   float tot = 0.f;
   for (int g0 = 0; g0 < groups; g0 += 16) {  // 16 loads in flight, added in group order
     float v[16];
@@ -127,7 +128,7 @@ __global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part
 #pragma unroll
     for (int u = 0; u < 16; ++u) tot += v[u];
   }
-  rstd[row] = 1.0f / sqrtf(tot * inv_H + eps);
+  rstd[row] = live ? 1.0f / sqrtf(tot * inv_H + eps) : 0.f;  // a padding row's sum is 0: no 1/0 when eps == 0
 }
 
 // ----------------------------------------------------------------------------
@@ -517,9 +518,9 @@ hipError_t mfma_prefill_end(const float *xres, const bf16_t *delta_bf, bf16_t *h
   return hipGetLastError();
 }
 
-hipError_t mfma_rstd(const float *ssq_part, float *rstd, int rows, int H, float eps, hipStream_t s) {
+hipError_t mfma_rstd(const float *ssq_part, float *rstd, const int *row_ext, int rows, int H, float eps, hipStream_t s) {
   if (rows == 0) return hipSuccess;
-  k_rstd<<<(rows + 255) / 256, 256, 0, s>>>(ssq_part, rstd, rows, H / 64, 1.0f / (float)H, eps);
+  k_rstd<<<(rows + 255) / 256, 256, 0, s>>>(ssq_part, rstd, row_ext, rows, H / 64, 1.0f / (float)H, eps);
   return hipGetLastError();
 }
 

@@ -145,14 +145,14 @@ hyp_status_t hypsched_simulate(int32_t n_tasks, const double *arrivals, int32_t 
                                const uint8_t *available, const double *transfer, int32_t *node_out, double *finish_out) {
   if (!arrivals || !F || !m_act || !nodes_per_tier || !C || !M || !node_out || !finish_out) return HYP_EINVAL;
   if (n_tasks < 1 || n_tiers < 1 || (n_tiers > 1 && !transfer)) return HYP_EINVAL;
-  std::vector<int> first(n_tiers + 1, 0);
-  for (int j = 0; j < n_tiers; ++j) {
-    if (nodes_per_tier[j] < 1) return HYP_EINVAL;
-    first[j + 1] = first[j] + nodes_per_tier[j];
-  }
-  for (int k = 0; k < first[n_tiers]; ++k)
-    if (!(C[k] > 0.0)) return HYP_EINVAL;
   try {
+    std::vector<int> first(n_tiers + 1, 0);
+    for (int j = 0; j < n_tiers; ++j) {
+      if (nodes_per_tier[j] < 1) return HYP_EINVAL;
+      first[j + 1] = first[j] + nodes_per_tier[j];
+    }
+    for (int k = 0; k < first[n_tiers]; ++k)
+      if (!(C[k] > 0.0)) return HYP_EINVAL;
     std::vector<std::deque<Held>> held(first[n_tiers]);
     std::priority_queue<Event, std::vector<Event>, std::greater<Event>> events;
     for (int q = 0; q < n_tasks; ++q) {

@@ -6,8 +6,10 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <string>
+#include <unordered_set>
 #include <vector>
 
 #include "common.h"
@@ -43,7 +45,16 @@ struct Layout {
   int chunk_keys = 128; // keys per chunk
   int ks_qkv = 1, ks_o = 1, ks_gu = 1, ks_d = 1;
   int fbw_o = 2, fbw_d = 2;  // 32-row blocks per workgroup of the two residual decode GEMMs
+  size_t partial_bytes = 0, attn_part_bytes = 0, counters_bytes = 0;
   size_t total = 0;
+};
+
+// The temporaries one decode step of the MFMA path works in (everything but weights, caches,
+// position tables and cached lengths), carved from the stage's workspace.
+struct DecScratch {
+  float *xres = nullptr, *ssq = nullptr, *partial = nullptr, *attn_part = nullptr;
+  unsigned *counters = nullptr;
+  bf16_t *y = nullptr, *attn = nullptr, *m = nullptr, *qdec = nullptr;
 };
 
 // The MFMA kernels cover bf16 stages shaped like the models of Table I: head_dim
@@ -142,11 +153,14 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.ks_d = L.fbw_d == 1 ? 1 : mfma_gemv_ksplit((int)H, (int)I, c.max_batch);
     size_t pf = std::max(std::max((size_t)L.ks_qkv * (qd + 2 * kvd), (size_t)L.ks_o * H),
                          std::max((size_t)L.ks_gu * 2 * I, (size_t)L.ks_d * H));
-    L.partial = take(sizeof(float) * pf * 32 * 2);  // room for twice the slices (row groups split finer at the end of a launch)
+    L.partial_bytes = sizeof(float) * pf * 32 * 2;  // room for twice the slices (row groups split finer at the end of a launch)
+    L.partial = take(L.partial_bytes);
     L.chunk_keys = mfma_decode_chunk_keys(c.max_seq, c.max_batch * c.n_kv_heads);
     L.max_chunks = (c.max_seq + L.chunk_keys - 1) / L.chunk_keys;
-    L.attn_part = take(sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks));
-    L.counters = take(sizeof(unsigned) * (2 * I / 64 + (qd + 2 * kvd) / 64 + H / 32));
+    L.attn_part_bytes = sizeof(float) * mfma_attn_decode_part_floats(c.n_q_heads, c.max_batch, L.max_chunks);
+    L.attn_part = take(L.attn_part_bytes);
+    L.counters_bytes = sizeof(unsigned) * (2 * I / 64 + (qd + 2 * kvd) / 64 + H / 32);
+    L.counters = take(L.counters_bytes);
     L.gemm_counters = take(sizeof(unsigned) * kGemmSplitMaxTiles);  // zeroed together with `counters`
     L.ssq = take(sizeof(float) * 32 * (H / 32));
     L.gemm_ws = take(mfma_gemm_split_ws_bytes());
@@ -203,6 +217,7 @@ struct hyp_stage {
   };
   std::vector<DecGraph> dec_graphs;
   hipStream_t cap_stream = nullptr;  // recording only (the null stream cannot be captured); nothing runs on it
+  DecScratch dec_ws;  // MFMA path: where a decode step keeps its temporaries (in the workspace)
   int batch;
   bool prefilled;
   std::string err;
@@ -351,14 +366,14 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
     r.xres = xres; r.row_ext = row_ext; r.ssq_part = ssq_part;
     r.gain = at<bf16_t>(st, p.g2);
     PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_RESID, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, y, d.H, r, s));
-    PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, rows, d.H, d.eps, s));
+    PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, row_ext, rows, d.H, d.eps, s));
     GemmEpilogue g = split;
     g.rstd = rstd;
     PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, g, s));
     if (!last) {
       r.gain = at<bf16_t>(st, L.layers[l + 1].g1);
       PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_RESID, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, y, d.H, r, s));
-      PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, rows, d.H, d.eps, s));
+      PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, row_ext, rows, d.H, d.eps, s));
     } else {
       PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, split, s));
       PROF(st, HYP_K_ADD_NORM, mfma_prefill_end(xres, delta, (bf16_t *)hidden_out, row_ext, rows, d.H, s));
@@ -370,19 +385,19 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
 // One decode step through the MFMA kernels (a single block of 32 token rows):
 // 1 + 5 launches per block, every reduction finished inside the kernel that
 // produced it.
-hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const void *hidden_in, void *hidden_out, bool begin,
-                              bool layers) {
+hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const DecScratch &sc, const void *hidden_in, void *hidden_out,
+                              bool begin, bool layers) {
   const Dims &d = st->dm;
   const Layout &L = st->L;
   DecGemv base;
-  base.partial = at<float>(st, L.partial);
-  base.counters = at<unsigned>(st, L.counters);
+  base.partial = sc.partial;
+  base.counters = sc.counters;
   base.batch = st->batch;
   base.eps = d.eps;
   base.H = d.H;
-  base.xres = at<float>(st, L.xres);
-  float *ssq = at<float>(st, L.ssq);
-  bf16_t *y = at<bf16_t>(st, L.y), *attn = at<bf16_t>(st, L.attn), *m = at<bf16_t>(st, L.m);
+  base.xres = sc.xres;
+  float *ssq = sc.ssq;
+  bf16_t *y = sc.y, *attn = sc.attn, *m = sc.m;
   CacheGeom geom = cache_geom(st);
   if (begin)
     PROF(st, HYP_K_ADD_NORM, mfma_dec_begin((const bf16_t *)hidden_in, base.xres, at<bf16_t>(st, L.layers[0].g1), y, ssq,
@@ -394,9 +409,9 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const void *hidden_i
     a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.ksplit = L.ks_qkv; a.max_ksplit = 2 * a.ksplit;
     a.ssq_in = ssq; a.n_ssq = d.H / (l == 0 ? 64 : 32 * L.fbw_d);  // written by the opening kernel / the previous down GEMM
     a.lens = at<int>(st, L.lens); a.cos_tab = at<float>(st, L.cos_tab); a.sin_tab = at<float>(st, L.sin_tab);
-    a.qdec = at<bf16_t>(st, L.qdec); a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
+    a.qdec = sc.qdec; a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
     PROF(st, HYP_K_GEMV_QKV, mfma_dec_gemv(DEC_QKV, a, s));
-    PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(a.qdec, Kc, Vc, geom, a.lens, at<float>(st, L.attn_part),
+    PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(a.qdec, Kc, Vc, geom, a.lens, sc.attn_part,
                                                  attn, d.nq, d.nkv, st->batch,
                                                  L.max_chunks, L.chunk_keys, s));
     DecGemv o = base;
@@ -438,10 +453,10 @@ hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
   HIP_TRY(st, hipStreamIsCapturing(s, &cap));
   bool use_graph = st->prof_mask == 0 && cap == hipStreamCaptureStatusNone && !(st->cfg.flags & HYP_FLAG_NO_GRAPH);
-  if (!use_graph) return decode_step_mfma(st, s, hidden_in, hidden_out, true, true);
+  if (!use_graph) return decode_step_mfma(st, s, st->dec_ws, hidden_in, hidden_out, true, true);
   // the first kernel reads the caller's input and stays outside the recording, so a
   // new input address every step does not force a new graph
-  hyp_status_t rc0 = decode_step_mfma(st, s, hidden_in, hidden_out, true, false);
+  hyp_status_t rc0 = decode_step_mfma(st, s, st->dec_ws, hidden_in, hidden_out, true, false);
   if (rc0 != HYP_OK) return rc0;
   // a few recorded graphs, keyed by what is baked into their kernel arguments
   hyp_stage::DecGraph *g = nullptr;
@@ -456,7 +471,7 @@ hyp_status_t run_decode_mfma(hyp_stage *st, const void *hidden_in, void *hidden_
     n.batch = st->batch; n.out = hidden_out;
     if (!st->cap_stream) HIP_TRY(st, hipStreamCreateWithFlags(&st->cap_stream, hipStreamNonBlocking));
     HIP_TRY(st, hipStreamBeginCapture(st->cap_stream, hipStreamCaptureModeThreadLocal));
-    hyp_status_t rc = decode_step_mfma(st, st->cap_stream, hidden_in, hidden_out, false, true);
+    hyp_status_t rc = decode_step_mfma(st, st->cap_stream, st->dec_ws, hidden_in, hidden_out, false, true);
     hipError_t e = hipStreamEndCapture(st->cap_stream, &n.graph);
     if (rc != HYP_OK) { drop_decode_graph(n); return rc; }
     if (e != hipSuccess) { drop_decode_graph(n); return fail(st, HYP_EDEVICE, std::string("hipStreamEndCapture: ") + hipGetErrorString(e)); }
@@ -506,11 +521,23 @@ hyp_status_t wait_upload(hyp_stage *st) {
   return HYP_OK;
 }
 
-}  // namespace
+// Handles this library has created and not yet destroyed.  Every entry point looks its
+// argument up here first, so a stale or foreign pointer (a stage destroyed twice, say) is
+// refused with HYP_EINVAL instead of being dereferenced.
+std::mutex g_live_mu;
+std::unordered_set<const hyp_stage *> g_live;
+bool is_live(const hyp_stage *st) {
+  std::lock_guard<std::mutex> lock(g_live_mu);
+  return g_live.count(st) != 0;
+}
+#define LIVE_OR_RETURN(st)                                                         \
+  do {                                                                             \
+    if (!(st)) return fail(nullptr, HYP_EINVAL, "stage is NULL");                  \
+    if (!is_live(st)) return fail(nullptr, HYP_EINVAL, "not a live stage handle"); \
+  } while (0)
 
-extern "C" {
 
-size_t stage_workspace_bytes(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end) {
+size_t do_stage_workspace_bytes(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end) {
   std::string err;
   if (check_config(cfg, l_start, l_end, err) != HYP_OK) { g_create_error = err; return 0; }
   Layout L;
@@ -518,7 +545,7 @@ size_t stage_workspace_bytes(const hyp_stage_config_t *cfg, int32_t l_start, int
   return L.total;
 }
 
-hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end,
+hyp_status_t do_stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end,
                           const hyp_layer_weights_t *layers, void *workspace, size_t workspace_bytes,
                           void *hip_stream, hyp_stage_t **out) {
   if (out) *out = nullptr;
@@ -571,6 +598,12 @@ hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_
   if (st->mfma) {
     hipError_t e = mfma_gemm_init();
     if (e != hipSuccess) { st->err = std::string("kernel attributes: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
+    // where a decode step keeps its temporaries: in the workspace ...
+    const Layout &L = st->L;
+    DecScratch &w = st->dec_ws;
+    w.xres = at<float>(st, L.xres); w.ssq = at<float>(st, L.ssq); w.partial = at<float>(st, L.partial);
+    w.attn_part = at<float>(st, L.attn_part); w.counters = at<unsigned>(st, L.counters);
+    w.y = at<bf16_t>(st, L.y); w.attn = at<bf16_t>(st, L.attn); w.m = at<bf16_t>(st, L.m); w.qdec = at<bf16_t>(st, L.qdec);
     rc = pack_weights_mfma(st, layers);
   } else {
     rc = copy_weights(st, layers);
@@ -600,13 +633,17 @@ hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_
     if (e == hipSuccess) e = hipStreamSynchronize(st->stream);  // host vectors die here
     if (e != hipSuccess) { st->err = std::string("table upload: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
   }
+  {
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    g_live.insert(st);
+  }
   *out = st;
   return HYP_OK;
 }
 
-hyp_status_t stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t *seq_lens,
+hyp_status_t do_stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t *seq_lens,
                            int32_t batch, void *hidden_out) {
-  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+  LIVE_OR_RETURN(st);
   if (!hidden_in || !seq_lens || !hidden_out) return fail(st, HYP_EINVAL, "NULL argument");
   if (batch < 1 || batch > st->cfg.max_batch) return fail(st, HYP_ECAPACITY, "batch outside 1..max_batch");
   int64_t total = 0;
@@ -682,25 +719,31 @@ hyp_status_t stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t
   return HYP_OK;
 }
 
-hyp_status_t stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
-  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+hyp_status_t check_decode_args(hyp_stage *st, const void *hidden_in, void *hidden_out) {
   if (!hidden_in || !hidden_out) return fail(st, HYP_EINVAL, "NULL argument");
   if (!st->prefilled) return fail(st, HYP_ESTATE, "stage_decode_step before stage_prefill");
   for (int b = 0; b < st->batch; ++b)
     if (st->lens[b] >= st->cfg.max_seq)
       return fail(st, HYP_ECAPACITY, "request " + std::to_string(b) + " already holds max_seq tokens");
+  return HYP_OK;
+}
+
+hyp_status_t do_stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
+  LIVE_OR_RETURN(st);
+  hyp_status_t rc = check_decode_args(st, hidden_in, hidden_out);
+  if (rc != HYP_OK) return rc;
   const int *iota = at<int>(st, st->L.iota), *lens = at<int>(st, st->L.lens);
-  hyp_status_t rc = st->mfma   ? run_decode_mfma(st, hidden_in, hidden_out)
-                    : st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, st->batch, iota, lens)
-                               : run_plain<float>(st, hidden_in, hidden_out, st->batch, iota, lens);
+  rc = st->mfma   ? run_decode_mfma(st, hidden_in, hidden_out)
+       : st->bf16 ? run_plain<bf16_t>(st, hidden_in, hidden_out, st->batch, iota, lens)
+                  : run_plain<float>(st, hidden_in, hidden_out, st->batch, iota, lens);
   if (rc != HYP_OK) return rc;
   if (!st->mfma) HIP_TRY(st, advance_lens(at<int>(st, st->L.lens), st->batch, st->stream));  // the MFMA path's last kernel does it
   for (int b = 0; b < st->batch; ++b) st->lens[b] += 1;
   return HYP_OK;
 }
 
-hyp_status_t stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {
-  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+hyp_status_t do_stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {
+  LIVE_OR_RETURN(st);
   if (!k_out || !v_out) return fail(st, HYP_EINVAL, "NULL argument");
   if (layer < 0 || layer >= st->n_layers) return fail(st, HYP_EINVAL, "layer outside the stage");
   if (!st->prefilled || request < 0 || request >= st->batch) return fail(st, HYP_ESTATE, "no such request");
@@ -718,23 +761,23 @@ hyp_status_t stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, vo
   return HYP_OK;
 }
 
-hyp_status_t stage_context_len(const hyp_stage_t *st, int32_t request, int32_t *len_out) {
-  if (!st || !len_out) return HYP_EINVAL;
+hyp_status_t do_stage_context_len(const hyp_stage_t *st, int32_t request, int32_t *len_out) {
+  if (!st || !len_out || !is_live(st)) return HYP_EINVAL;
   if (!st->prefilled || request < 0 || request >= st->batch) return HYP_ESTATE;
   *len_out = st->lens[request];
   return HYP_OK;
 }
 
-hyp_status_t stage_profile(hyp_stage_t *st, uint32_t class_mask) {
-  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+hyp_status_t do_stage_profile(hyp_stage_t *st, uint32_t class_mask) {
+  LIVE_OR_RETURN(st);
   HIP_TRY(st, hipStreamSynchronize(st->stream));
   st->prof_mask = class_mask;
   st->prof_used = 0;
   return HYP_OK;
 }
 
-hyp_status_t stage_profile_read(hyp_stage_t *st, int32_t kernel_class, double *total_ms, int64_t *launches) {
-  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+hyp_status_t do_stage_profile_read(hyp_stage_t *st, int32_t kernel_class, double *total_ms, int64_t *launches) {
+  LIVE_OR_RETURN(st);
   if (!total_ms || !launches || kernel_class < 0 || kernel_class >= HYP_K_COUNT) return fail(st, HYP_EINVAL, "bad argument");
   HIP_TRY(st, hipStreamSynchronize(st->stream));
   double tot = 0;
@@ -751,8 +794,12 @@ hyp_status_t stage_profile_read(hyp_stage_t *st, int32_t kernel_class, double *t
   return HYP_OK;
 }
 
-hyp_status_t stage_destroy(hyp_stage_t *st) {
-  if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+hyp_status_t do_stage_destroy(hyp_stage_t *st) {
+  {
+    if (!st) return fail(nullptr, HYP_EINVAL, "stage is NULL");
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    if (g_live.erase(st) == 0) return fail(nullptr, HYP_EINVAL, "not a live stage handle (destroyed twice?)");
+  }
   if (st->upload_done) (void)hipEventDestroy(st->upload_done);
   if (st->h_stage) (void)hipHostFree(st->h_stage);
   for (auto &ps : st->prof) { (void)hipEventDestroy(ps.a); (void)hipEventDestroy(ps.b); }
@@ -762,10 +809,86 @@ hyp_status_t stage_destroy(hyp_stage_t *st) {
   return HYP_OK;
 }
 
-const char *stage_last_error(const hyp_stage_t *st) {
+const char *do_stage_last_error(const hyp_stage_t *st) {
+  if (st && !is_live(st)) return "not a live stage handle";
   return st ? st->err.c_str() : g_create_error.c_str();
 }
 
-int32_t stage_uses_mfma(const hyp_stage_t *st) { return st && st->mfma ? 1 : 0; }
+int32_t do_stage_uses_mfma(const hyp_stage_t *st) { return st && is_live(st) && st->mfma ? 1 : 0; }
+
+// No C++ exception may cross the C ABI: every entry point runs its body under this guard
+// (the bodies allocate host memory through std::string / std::vector).
+template <typename F> hyp_status_t guarded(F &&body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    return HYP_ENOMEM;
+  } catch (...) {
+    return HYP_EDEVICE;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t stage_workspace_bytes(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end) {
+  try {
+    return do_stage_workspace_bytes(cfg, l_start, l_end);
+  } catch (...) {
+    return 0;
+  }
+}
+
+hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end,
+                          const hyp_layer_weights_t *layers, void *workspace, size_t workspace_bytes,
+                          void *hip_stream, hyp_stage_t **out) {
+  return guarded([&] { return do_stage_create(cfg, l_start, l_end, layers, workspace, workspace_bytes, hip_stream, out); });
+}
+
+hyp_status_t stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t *seq_lens, int32_t batch,
+                           void *hidden_out) {
+  return guarded([&] { return do_stage_prefill(st, hidden_in, seq_lens, batch, hidden_out); });
+}
+
+hyp_status_t stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
+  return guarded([&] { return do_stage_decode_step(st, hidden_in, hidden_out); });
+}
+
+hyp_status_t stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {
+  return guarded([&] { return do_stage_export_kv(st, layer, request, k_out, v_out); });
+}
+
+hyp_status_t stage_context_len(const hyp_stage_t *st, int32_t request, int32_t *len_out) {
+  return guarded([&] { return do_stage_context_len(st, request, len_out); });
+}
+
+hyp_status_t stage_profile(hyp_stage_t *st, uint32_t class_mask) {
+  return guarded([&] { return do_stage_profile(st, class_mask); });
+}
+
+hyp_status_t stage_profile_read(hyp_stage_t *st, int32_t kernel_class, double *total_ms, int64_t *launches) {
+  return guarded([&] { return do_stage_profile_read(st, kernel_class, total_ms, launches); });
+}
+
+hyp_status_t stage_destroy(hyp_stage_t *st) {
+  return guarded([&] { return do_stage_destroy(st); });
+}
+
+const char *stage_last_error(const hyp_stage_t *st) {
+  try {
+    return do_stage_last_error(st);
+  } catch (...) {
+    return "";
+  }
+}
+
+int32_t stage_uses_mfma(const hyp_stage_t *st) {
+  try {
+    return do_stage_uses_mfma(st);
+  } catch (...) {
+    return 0;
+  }
+}
 
 }  // extern "C"

@@ -82,3 +82,20 @@ def test_null_and_range_arguments():
     assert lib.stage_decode_step(None, None, None) == binding.HYP_EINVAL
     assert lib.stage_destroy(None) == binding.HYP_EINVAL
     assert lib.stage_uses_mfma(None) == 0
+
+
+def test_foreign_handles_are_refused_not_dereferenced():
+    # every entry point looks its handle up among the live stages first: a pointer the library
+    # never handed out (or one it already destroyed) is HYP_EINVAL
+    lib = hyp.load_library()
+    junk = C.create_string_buffer(4096)
+    h = C.c_void_p(C.addressof(junk))
+    assert lib.stage_destroy(h) == binding.HYP_EINVAL
+    assert lib.stage_decode_step(h, h, h) == binding.HYP_EINVAL
+    assert lib.stage_prefill(h, h, None, 1, h) == binding.HYP_EINVAL
+    assert lib.stage_export_kv(h, 0, 0, h, h) == binding.HYP_EINVAL
+    n = C.c_int32()
+    assert lib.stage_context_len(h, 0, C.byref(n)) == binding.HYP_EINVAL
+    assert lib.stage_profile(h, 0) == binding.HYP_EINVAL
+    assert lib.stage_uses_mfma(h) == 0
+    assert b"live" in lib.stage_last_error(h)

@@ -27,9 +27,11 @@ def sample_rows(L, rng, n_random=6):
     return rows
 
 
-def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE):
+def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE, cap=None):
+    """`cap` = per-request capacity of the stage: it fixes the decode attention's chunking, so
+    the tests of a bench workload pass the capacity the bench creates its stage with."""
     B, T = len(lens), sum(lens)
-    cap = max(lens) + decode_steps
+    cap = cap or max(lens) + decode_steps
     x = synth.hidden_states(T, SHAPE, seed)
     gst = make_gpu_stage(SHAPE, [layer], B, cap, T)
     assert gst.uses_mfma()
@@ -63,6 +65,7 @@ def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE):
             assert e <= TOL, (s, b, e)
             worst = max(worst, e)
     gst.destroy()
+    print(f"\nlens {lens[:4]}{'...' if len(lens) > 4 else ''} cap {cap}: worst rel err {worst:.3e}")
     return worst
 
 
@@ -78,19 +81,59 @@ def test_short_prompts_full_width_split_k_gemms(phi3_layer):
 
 
 def test_c3_layer_8x2048_sampled_rows_then_decode(phi3_layer):
-    check_requests(phi3_layer, [2048] * 8, 9200, sample_reqs=[0, 5], decode_steps=2)
+    wl = synth.WORKLOADS["c3_stage10"]
+    check_requests(phi3_layer, [2048] * 8, 9200, sample_reqs=[0, 5], decode_steps=2, cap=2048 + wl.decode_steps)
 
 
 def test_c4_ragged_batch32_decode_at_long_context(phi3_layer):
     lens = synth.WORKLOADS["c4_decode_heavy"].lengths()
     assert len(lens) == 32 and min(lens) >= 1024 and max(lens) <= 4096
     longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
-    check_requests(phi3_layer, lens, 9300, sample_reqs=[longest, shortest], decode_steps=2)
+    check_requests(phi3_layer, lens, 9300, sample_reqs=[longest, shortest], decode_steps=2,
+                   cap=max(lens) + synth.WORKLOADS["c4_decode_heavy"].decode_steps)
 
 
 def test_c5_long_context_8192_sampled_rows_then_decode(phi3_layer):
     # one long request (the 8192-token prompts of the long-sequence workload) next to a short one
     check_requests(phi3_layer, [8192, 300], 9400, sample_reqs=[0, 1], decode_steps=2)
+
+
+def test_c5_launch_shape_batch8_capacity_9216(phi3_layer):
+    # the stage the long-sequence workload creates: 8 resident requests of capacity 8192 + 1024,
+    # which makes the decode attention run 1024-key chunks, nine of them for the long request;
+    # seven short requests keep the oracle's share affordable
+    wl = synth.WORKLOADS["c5_long"]
+    lens = [8192, 1, 31, 64, 100, 333, 1024, 1500]
+    check_requests(phi3_layer, lens, 9450, sample_reqs=[0, 2, 7], decode_steps=2, cap=8192 + wl.decode_steps)
+
+
+def test_three_blocks_at_full_width_whole_tensor():
+    """A stage of three Phi-3-medium-shaped blocks over short prompts, every element against
+    the oracle: inside a stage the down projection's residual epilogue hands its output and
+    norm statistics straight to the next block's QKV projection (prefill and decode), which a
+    one-block stage never exercises at widths 5120 / 17920."""
+    seed = synth.WORKLOADS["c3_stage10"].seed
+    layers = [synth.layer_weights(SHAPE, l, seed) for l in range(3)]
+    lens, steps = [64, 17], 2
+    x = synth.hidden_states(sum(lens), SHAPE, 9600)
+    ost = orc.Stage(SHAPE, layers, 2, 80, "f32")
+    gst = make_gpu_stage(SHAPE, layers, 2, 80, sum(lens))
+    assert gst.uses_mfma()
+    ref = ost.prefill(x, lens)
+    got = to_host(gst.prefill(to_dev(x, "bf16"), lens))
+    errs = [rel_err(got, ref), rel_err(got - x, ref - x)]
+    for l in range(3):
+        for b in range(2):
+            k, v = gst.export_kv(l, b)
+            errs += [rel_err(to_host(k), ost.K[l, b, :lens[b]]), rel_err(to_host(v), ost.V[l, b, :lens[b]])]
+    for s in range(steps):
+        xd = synth.hidden_states(2, SHAPE, 9601 + s)
+        ref = ost.decode_step(xd)
+        got = to_host(gst.decode_step(to_dev(xd, "bf16")))
+        errs += [rel_err(got, ref), rel_err(got - xd, ref - xd)]
+    gst.destroy()
+    print(f"\nthree full-width blocks: prefill {errs[0]:.3e} (update {errs[1]:.3e}), worst of all {max(errs):.3e}")
+    assert max(errs) <= TOL, errs
 
 
 def test_llama3_8b_shaped_block_sampled_rows_then_decode():

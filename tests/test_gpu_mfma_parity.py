@@ -208,3 +208,11 @@ def test_mfma_three_layer_stage_composition():
     got = to_host(b.prefill(a.prefill(to_dev(x, "bf16"), lens), lens))
     check(got, ref, x, "bf16", "chained stages")
     a.destroy(); b.destroy()
+
+
+def test_mfma_rms_eps_zero_with_padded_prompts():
+    # eps = 0 is admitted: the rows that pad a prompt to a multiple of 64 have a zero sum of
+    # squares and must not turn into 1/0 on their way into the caches
+    shape = dataclasses.replace(SHAPE_G2, rms_eps=0.0)
+    _, gst = run_mfma(shape, 2, [37, 130, 1], 3, 780)
+    gst.destroy()

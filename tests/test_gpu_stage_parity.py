@@ -206,4 +206,8 @@ def test_state_machine_and_capacity_errors():
     assert st.context_len(0) == 3
     with pytest.raises(hyp.HypError):
         st.context_len(1)
+    # destroying a stage twice is refused, and the dead handle is refused everywhere
+    lib, handle = hyp.load_library(), st.handle
     st.destroy()
+    assert lib.stage_destroy(handle) == binding.HYP_EINVAL
+    assert lib.stage_decode_step(handle, xd.data_ptr(), xd.data_ptr()) == binding.HYP_EINVAL

@@ -143,6 +143,20 @@ HYP_API hyp_status_t stage_prefill(hyp_stage_t *stage, const void *hidden_in, co
  * max_seq tokens; nothing is changed), HYP_EINVAL, HYP_EDEVICE. */
 HYP_API hyp_status_t stage_decode_step(hyp_stage_t *stage, const void *hidden_in, void *hidden_out);
 
+/* stage_decode_step for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments, same result bit for bit, but
+ * the step's temporaries (partial sums and arrival counters of the split GEMVs, per-chunk
+ * attention results, the block's activations of the <= 32 tokens) live in a 32 MiB array that is
+ * part of the library's device image instead of the workspace, the kernels are launched one by
+ * one (no graph is recorded or instantiated), no events are created, and the call performs no
+ * device or host allocation.  Every stage and every call on one GPU shares that GPU's array:
+ * calls that overlap on one GPU (two streams, two threads) race; calls ordered on one stream or
+ * by events are fine.  Serves stages that run the MFMA kernels (stage_uses_mfma).
+ * Errors: as stage_decode_step, plus HYP_ESHAPE (stage on the shape-generic kernels) and
+ * HYP_ECAPACITY when one step's temporaries exceed the array (the Phi-3-medium-shaped and
+ * Llama3-8B-shaped blocks at up to 32 requests fit); nothing is changed then. */
+HYP_API hyp_status_t stage_decode_step_noalloc(hyp_stage_t *stage, const void *hidden_in, void *hidden_out);
+
 /* Copy the cached keys (post-RoPE) and values of one request and one block of
  * the stage (layer in [0, l_end - l_start)) to k_out / v_out, device,
  * [context_len, n_kv_heads*head_dim] row-major in the stage dtype.  This is what

@@ -20,7 +20,7 @@ HYP_F32, HYP_BF16 = 0, 1
 HYP_FLAG_PLAIN_KERNELS = 1
 HYP_FLAG_NO_GRAPH = 2
 
-EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_decode_step",
+EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_decode_step", "stage_decode_step_noalloc",
            "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",
            "stage_uses_mfma", "stage_profile", "stage_profile_read",
            "hyp_measure_mfma_ceiling", "hyp_measure_hbm_read_ceiling")
@@ -84,6 +84,8 @@ def load_library() -> C.CDLL:
     lib.stage_prefill.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_void_p]
     lib.stage_decode_step.restype = C.c_int
     lib.stage_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.stage_decode_step_noalloc.restype = C.c_int
+    lib.stage_decode_step_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.stage_export_kv.restype = C.c_int
     lib.stage_export_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.stage_context_len.restype = C.c_int
@@ -143,6 +145,9 @@ class Stage:
 
     def decode_step(self, hidden_in, hidden_out=None):
         return stage_decode_step(self, hidden_in, hidden_out)
+
+    def decode_step_noalloc(self, hidden_in, hidden_out):
+        return stage_decode_step_noalloc(self, hidden_in, hidden_out)
 
     def export_kv(self, layer, request):
         return stage_export_kv(self, layer, request)
@@ -220,6 +225,15 @@ def stage_decode_step(stage: Stage, hidden_in: torch.Tensor, hidden_out: Optiona
         hidden_out = torch.empty_like(hidden_in)
     _validate_io(stage, hidden_in, hidden_out, None)
     status = load_library().stage_decode_step(stage.handle, hidden_in.data_ptr(), hidden_out.data_ptr())
+    _check(status, stage.handle)
+    return hidden_out
+
+
+def stage_decode_step_noalloc(stage: Stage, hidden_in: torch.Tensor, hidden_out: torch.Tensor) -> torch.Tensor:
+    """stage_decode_step with the step's temporaries in the library's static device array; the
+    caller supplies the output tensor, nothing is allocated."""
+    _validate_io(stage, hidden_in, hidden_out, None)
+    status = load_library().stage_decode_step_noalloc(stage.handle, hidden_in.data_ptr(), hidden_out.data_ptr())
     _check(status, stage.handle)
     return hidden_out
 

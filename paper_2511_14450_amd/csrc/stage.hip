@@ -17,9 +17,38 @@
 
 using namespace hyp;
 
+// Per-step temporaries of stage_decode_step_noalloc(): one array per GPU, shared by every
+// stage and every call on that GPU until the process ends.  Host code never uses this name as
+// an address; it uses what hipGetSymbolAddress() returns for the current device.
+constexpr size_t kNoAllocScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
 namespace {
 
 thread_local std::string g_create_error = "";
+
+// device address of `scratch` on each GPU, looked up once per device by stage_create
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch_of_current_device(void **out) {
+  *out = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -50,7 +79,8 @@ struct Layout {
 };
 
 // The temporaries one decode step of the MFMA path works in (everything but weights, caches,
-// position tables and cached lengths), carved from the stage's workspace.
+// position tables and cached lengths): either carved from the stage's workspace or from the
+// per-GPU static array.
 struct DecScratch {
   float *xres = nullptr, *ssq = nullptr, *partial = nullptr, *attn_part = nullptr;
   unsigned *counters = nullptr;
@@ -208,6 +238,7 @@ struct hyp_stage {
   std::vector<ProfSlot> prof;
   size_t prof_used = 0;
   uint32_t prof_mask = 0;
+  bool prof_off = false;  // set around calls that must not create events
   // recorded decode steps (kernel arguments baked in), replayed when they match
   struct DecGraph {
     hipGraph_t graph = nullptr;
@@ -217,7 +248,10 @@ struct hyp_stage {
   };
   std::vector<DecGraph> dec_graphs;
   hipStream_t cap_stream = nullptr;  // recording only (the null stream cannot be captured); nothing runs on it
-  DecScratch dec_ws;  // MFMA path: where a decode step keeps its temporaries (in the workspace)
+  // MFMA path: where a decode step keeps its temporaries - in the workspace, or (for
+  // stage_decode_step_noalloc) in the GPU's static array when `static_bytes` of it suffice
+  DecScratch dec_ws, dec_static;
+  size_t static_bytes = 0;
   int batch;
   bool prefilled;
   std::string err;
@@ -241,7 +275,7 @@ hyp_status_t fail(hyp_stage *st, hyp_status_t code, const std::string &msg) {
 // pair of events recorded on the stage's stream.
 hipError_t prof_begin(hyp_stage *st, int cls, int *slot) {
   *slot = -1;
-  if (!(st->prof_mask & (1u << cls))) return hipSuccess;
+  if (!(st->prof_mask & (1u << cls)) || st->prof_off) return hipSuccess;
   if (st->prof_used == st->prof.size()) {
     hyp_stage::ProfSlot ps;
     hipError_t e = hipEventCreate(&ps.a);
@@ -604,6 +638,27 @@ hyp_status_t do_stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int
     w.xres = at<float>(st, L.xres); w.ssq = at<float>(st, L.ssq); w.partial = at<float>(st, L.partial);
     w.attn_part = at<float>(st, L.attn_part); w.counters = at<unsigned>(st, L.counters);
     w.y = at<bf16_t>(st, L.y); w.attn = at<bf16_t>(st, L.attn); w.m = at<bf16_t>(st, L.m); w.qdec = at<bf16_t>(st, L.qdec);
+    // ... or, for stage_decode_step_noalloc, in this GPU's static array, if that is large enough
+    void *sbase = nullptr;
+    e = static_scratch_of_current_device(&sbase);
+    if (e != hipSuccess) { st->err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
+    {
+      const size_t es = 2, H = d.H;
+      size_t off = 0;
+      auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+      const size_t o_cnt = take(L.counters_bytes), o_xres = take(sizeof(float) * 32 * H), o_ssq = take(sizeof(float) * 32 * (H / 32)),
+                   o_y = take(es * 32 * H), o_attn = take(es * 32 * (size_t)d.qd), o_m = take(es * 32 * (size_t)d.I),
+                   o_q = take(es * (size_t)d.max_batch * d.nkv * 32 * 128), o_part = take(L.partial_bytes),
+                   o_ap = take(L.attn_part_bytes);
+      st->static_bytes = off;
+      if (off <= kNoAllocScratchBytes) {
+        char *b = (char *)sbase;
+        DecScratch &t = st->dec_static;
+        t.counters = (unsigned *)(b + o_cnt); t.xres = (float *)(b + o_xres); t.ssq = (float *)(b + o_ssq);
+        t.y = (bf16_t *)(b + o_y); t.attn = (bf16_t *)(b + o_attn); t.m = (bf16_t *)(b + o_m); t.qdec = (bf16_t *)(b + o_q);
+        t.partial = (float *)(b + o_part); t.attn_part = (float *)(b + o_ap);
+      }
+    }
     rc = pack_weights_mfma(st, layers);
   } else {
     rc = copy_weights(st, layers);
@@ -742,6 +797,27 @@ hyp_status_t do_stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *
   return HYP_OK;
 }
 
+// The same step with its temporaries in the GPU's static array: kernel launches only - no
+// device or host allocation, no graph objects, no events.
+hyp_status_t do_stage_decode_step_noalloc(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
+  LIVE_OR_RETURN(st);
+  if (!st->mfma) return fail(st, HYP_ESHAPE, "stage_decode_step_noalloc serves stages that run the MFMA kernels");
+  if (st->static_bytes > kNoAllocScratchBytes)
+    return fail(st, HYP_ECAPACITY, "a decode step of this stage needs " + std::to_string(st->static_bytes) +
+                                       " bytes of temporaries; the static array holds " + std::to_string(kNoAllocScratchBytes));
+  hyp_status_t rc = check_decode_args(st, hidden_in, hidden_out);
+  if (rc != HYP_OK) return rc;
+  // the array keeps whatever the last call on this GPU left: the arrival counters must start at zero
+  // (a fill kernel, not a memset node, so that the call can be captured into a graph)
+  HIP_TRY(st, mfma_fill_zero(st->dec_static.counters, align_up(st->L.counters_bytes), st->stream));
+  st->prof_off = true;
+  rc = decode_step_mfma(st, st->stream, st->dec_static, hidden_in, hidden_out, true, true);
+  st->prof_off = false;
+  if (rc != HYP_OK) return rc;
+  for (int b = 0; b < st->batch; ++b) st->lens[b] += 1;
+  return HYP_OK;
+}
+
 hyp_status_t do_stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {
   LIVE_OR_RETURN(st);
   if (!k_out || !v_out) return fail(st, HYP_EINVAL, "NULL argument");
@@ -853,6 +929,10 @@ hyp_status_t stage_prefill(hyp_stage_t *st, const void *hidden_in, const int32_t
 
 hyp_status_t stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
   return guarded([&] { return do_stage_decode_step(st, hidden_in, hidden_out); });
+}
+
+hyp_status_t stage_decode_step_noalloc(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
+  return guarded([&] { return do_stage_decode_step_noalloc(st, hidden_in, hidden_out); });
 }
 
 hyp_status_t stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {

@@ -92,6 +92,7 @@ def test_foreign_handles_are_refused_not_dereferenced():
     h = C.c_void_p(C.addressof(junk))
     assert lib.stage_destroy(h) == binding.HYP_EINVAL
     assert lib.stage_decode_step(h, h, h) == binding.HYP_EINVAL
+    assert lib.stage_decode_step_noalloc(h, h, h) == binding.HYP_EINVAL
     assert lib.stage_prefill(h, h, None, 1, h) == binding.HYP_EINVAL
     assert lib.stage_export_kv(h, 0, 0, h, h) == binding.HYP_EINVAL
     n = C.c_int32()

@@ -37,6 +37,11 @@ KERNEL_TIMING = ("HIP events recorded by the library on the stage's stream aroun
                  "kernel's own time in a rocprofv3 trace)")
 
 
+def progress(msg):
+    """One line on stderr per finished part (the JSON line on stdout stays alone)."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 def traffic_file(workload):
     return os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
 
@@ -159,13 +164,16 @@ def run_workload(wl, steps, warmup, no_graph=False, traffic_calibration=False, p
         dst.copy_(src)      # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
+    progress(f"{wl.name}: stage created ({wl.n_layers} blocks), {warmup} warm-up + {steps} timed steps")
     for _ in range(warmup):
         step(False)
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        progress(f"{wl.name}: warm-up step done")
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for i in range(steps):
         step(True)
         torch.cuda.synchronize()
+        progress(f"{wl.name}: timed step {i + 1} of {steps} done")
         pre_ms.append(ev[0].elapsed_time(ev[1]))
         dec_ms.append(ev[1].elapsed_time(ev[2]))
     torch.cuda.synchronize()
@@ -242,6 +250,7 @@ def run_workload(wl, steps, warmup, no_graph=False, traffic_calibration=False, p
     stage.destroy()
     del stage, x, y, xd, yd
     torch.cuda.empty_cache()
+    progress(f"{wl.name}: per-kernel pass done")
     return out
 
 
@@ -367,6 +376,7 @@ def main():
             "hbm_stream_read_gbs": hyp.hyp_measure_hbm_read_ceiling(4),
             "gemm_gateup_kernel_constant_operands_tflops": gemm_constant_operands_tflops(wl),
         }
+        progress("measured ceilings done")
         if not overridden:
             # the other configurations, each timed over 1 warm-up + 2 steps (figures, not the headline value)
             others = [k for k in ("c3_stage10", "c4_decode_heavy", "n4_llama3_stage8", "c5_long") if k != args.workload]
@@ -375,6 +385,7 @@ def main():
             out["other_configs"] = [brief(run_workload(synth.WORKLOADS[k], 2, 1)) for k in others]
             out["other_configs"].append(prefill_only_line("c2_layer_prefill"))
     if not args.no_cpu_baseline:
+        progress("timing the CPU oracle on its sample")
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
 

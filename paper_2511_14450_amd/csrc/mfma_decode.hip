@@ -74,7 +74,8 @@ struct DecGemvParams {
 // gate and up) and for long K; 1 for the residual epilogues at short K, where 32-row workgroups with
 // a 10-tile window give as many waves with as much in flight as two slices of 64-row workgroups
 // would, without partial sums, counter and gather at the end.
-template <int EPI, int FBW>
+// CLS (a hyp_kernel_class_t) only gives each GEMM of a block its own kernel name in a trace.
+template <int EPI, int FBW, int CLS>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) k_dec_gemv(DecGemvParams p) {
   constexpr int UNROLL = FBW == 1 ? 10 : 5;
   constexpr int kGroupRows = FBW * 32;
@@ -463,7 +464,7 @@ int mfma_gemv_ksplit(int N, int K, int batch) {
 // without any split (same number of waves, same bytes in flight, no partial sums)
 int mfma_gemv_resid_fbw(int K) { return K / 16 / NW <= 112 && (K / 16) % NW == 0 ? 1 : 2; }
 
-hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s) {
+hipError_t mfma_dec_gemv(int epi, int cls, const DecGemv &a, hipStream_t s) {
   DecGemvParams p = {};
   p.W = a.W; p.x = a.x; p.partial = a.partial; p.counters = a.counters;
   p.N = a.N; p.KT = a.K / 16; p.ksplit = a.ksplit; p.tiles_per_wave = p.KT / (a.ksplit * NW); p.batch = a.batch;
@@ -481,18 +482,14 @@ hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s) {
       p.tiles_per_wave / 2 >= 10 && 2 * a.ksplit <= a.max_ksplit)
     p.groups1 = slots / a.ksplit;
   dim3 grid(p.groups1 * a.ksplit + (groups - p.groups1) * 2 * a.ksplit);
-  switch (epi) {
-    case DEC_QKV: k_dec_gemv<DEC_QKV, 2><<<grid, NW * 64, 0, s>>>(p); break;
-    case DEC_SWIGLU: k_dec_gemv<DEC_SWIGLU, 2><<<grid, NW * 64, 0, s>>>(p); break;
-    case DEC_RESID:
-      if (fbw == 1) k_dec_gemv<DEC_RESID, 1><<<grid, NW * 64, 0, s>>>(p);
-      else k_dec_gemv<DEC_RESID, 2><<<grid, NW * 64, 0, s>>>(p);
-      break;
-    default:
-      if (fbw == 1) k_dec_gemv<DEC_FINAL, 1><<<grid, NW * 64, 0, s>>>(p);
-      else k_dec_gemv<DEC_FINAL, 2><<<grid, NW * 64, 0, s>>>(p);
-      break;
-  }
+  bool launched = false;
+#define X(EPI, FBW, CLS) \
+  if (!launched && epi == EPI && fbw == FBW && cls == CLS) { k_dec_gemv<EPI, FBW, CLS><<<grid, NW * 64, 0, s>>>(p); launched = true; }
+  X(DEC_QKV, 2, HYP_K_GEMV_QKV) X(DEC_SWIGLU, 2, HYP_K_GEMV_GATEUP)
+  X(DEC_RESID, 1, HYP_K_GEMV_O) X(DEC_RESID, 2, HYP_K_GEMV_O)
+  X(DEC_RESID, 1, HYP_K_GEMV_DOWN) X(DEC_RESID, 2, HYP_K_GEMV_DOWN) X(DEC_FINAL, 1, HYP_K_GEMV_DOWN) X(DEC_FINAL, 2, HYP_K_GEMV_DOWN)
+#undef X
+  if (!launched) return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

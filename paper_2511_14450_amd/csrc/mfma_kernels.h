@@ -49,7 +49,8 @@ hipError_t mfma_rstd(const float *ssq_part, float *rstd, const int *row_ext, int
 hipError_t mfma_gemm_init();
 // out^T[N, rows] = W[N,K] X[rows,K]^T with the epilogue `epi`; rows % 32 == 0,
 // N % 256 == 0, K % 32 == 0, K >= 128
-hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
+// `cls` (a hyp_kernel_class_t) names the GEMM of the block; it selects a kernel symbol, not behaviour
+hipError_t mfma_gemm(int epi, int cls, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
                      int out_K, const GemmEpilogue &ep, hipStream_t s);
 
 // Causal GQA attention over the prompt (flash-style, scores never stored).
@@ -92,7 +93,7 @@ struct DecGemv {
   int H = 0;
   int *lens_advance = nullptr;  // DEC_FINAL: lengths to increment at the end of the step
 };
-hipError_t mfma_dec_gemv(int epi, const DecGemv &a, hipStream_t s);
+hipError_t mfma_dec_gemv(int epi, int cls, const DecGemv &a, hipStream_t s);  // cls: as for mfma_gemm
 int mfma_gemv_ksplit(int N, int K, int batch);
 int mfma_gemv_resid_fbw(int K);  // 1: run the residual GEMM of this K as unsplit 32-row workgroups
 // x = hidden_in ; xres = x ; y' = x * gain -> P(32, H) ; ssq_out[H/64][32]

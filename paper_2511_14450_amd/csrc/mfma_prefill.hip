@@ -192,7 +192,9 @@ __device__ __forceinline__ void store_block(bf16_t *out, int out_K, int tb, int 
   }
 }
 
-template <int EPI>
+// CLS (a hyp_kernel_class_t) does not change the code: it gives each GEMM of a block a kernel name of its
+// own, so that a trace tells the O projection from the down projection, which share an epilogue.
+template <int EPI, int CLS>
 __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;  // wave-uniform: scalar registers
@@ -530,15 +532,21 @@ constexpr int kGemmSplitUnits = 512;  // most (tile, slice) pairs of a split GEM
 // largest scratch a split GEMM can use: kGemmSplitUnits partial tiles of 256 x 256 fp32
 size_t mfma_gemm_split_ws_bytes() { return (size_t)kGemmSplitUnits * (WF * WT) * (FB * TB * 16 * 64) * sizeof(float); }
 
+// the (epilogue, class) pairs a block uses
+#define HYP_GEMM_VARIANTS(X)                                                                        \
+  X(EPI_QKV, HYP_K_GEMM_QKV) X(EPI_RESID, HYP_K_GEMM_O) X(EPI_SWIGLU, HYP_K_GEMM_GATEUP)            \
+  X(EPI_RESID, HYP_K_GEMM_DOWN) X(EPI_STORE, HYP_K_GEMM_DOWN)
+
 hipError_t mfma_gemm_init() {
-  hipError_t e = hipFuncSetAttribute((const void *)k_gemm<EPI_STORE>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_QKV>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
-  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+  hipError_t e = hipSuccess;
+#define X(EPI, CLS) \
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gemm<EPI, CLS>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+  HYP_GEMM_VARIANTS(X)
+#undef X
   return e;
 }
 
-hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
+hipError_t mfma_gemm(int epi, int cls, const bf16_t *X, const bf16_t *W, int rows, int N, int K, bf16_t *out,
                      int out_K, const GemmEpilogue &ep, hipStream_t s) {
   if (rows == 0) return hipSuccess;
   GemmParams p = {};
@@ -572,10 +580,12 @@ hipError_t mfma_gemm(int epi, const bf16_t *X, const bf16_t *W, int rows, int N,
   }
   p.split_ws = ep.split_ws; p.split_counters = ep.split_counters;
   int grid = p.tiles_grid * p.ksplit;
-  if (epi == EPI_STORE) k_gemm<EPI_STORE><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
-  else if (epi == EPI_SWIGLU) k_gemm<EPI_SWIGLU><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
-  else if (epi == EPI_RESID) k_gemm<EPI_RESID><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
-  else k_gemm<EPI_QKV><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p);
+  bool launched = false;
+#define X(EPI, CLS) \
+  if (!launched && epi == EPI && cls == CLS) { k_gemm<EPI, CLS><<<grid, WF * WT * 64, GEMM_LDS, s>>>(p); launched = true; }
+  HYP_GEMM_VARIANTS(X)
+#undef X
+  if (!launched) return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

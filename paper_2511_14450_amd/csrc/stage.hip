@@ -392,24 +392,24 @@ hyp_status_t run_prefill_mfma(hyp_stage *st, const void *hidden_in, void *hidden
     e.cos_tab = at<float>(st, L.cos_tab); e.sin_tab = at<float>(st, L.sin_tab);
     e.row_pos = at<int>(st, L.row_pos); e.row_req = at<int>(st, L.row_req);
     e.rstd = rstd;
-    PROF(st, HYP_K_GEMM_QKV, mfma_gemm(EPI_QKV, y, at<bf16_t>(st, p.wqkv), rows, d.qd + 2 * d.kvd, d.H, q, d.qd, e, s));
+    PROF(st, HYP_K_GEMM_QKV, mfma_gemm(EPI_QKV, HYP_K_GEMM_QKV, y, at<bf16_t>(st, p.wqkv), rows, d.qd + 2 * d.kvd, d.H, q, d.qd, e, s));
     PROF(st, HYP_K_ATTN_PREFILL, mfma_attn_prefill(q, e.Kc, e.Vc, geom, attn, at<PrefillTile>(st, L.tiles), n_tiles,
                                   at<int>(st, L.req_len), d.nq, d.nkv, s));
     // residual add, the next norm's gain and its statistics all happen in the epilogue
     GemmEpilogue r = split;
     r.xres = xres; r.row_ext = row_ext; r.ssq_part = ssq_part;
     r.gain = at<bf16_t>(st, p.g2);
-    PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_RESID, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, y, d.H, r, s));
+    PROF(st, HYP_K_GEMM_O, mfma_gemm(EPI_RESID, HYP_K_GEMM_O, attn, at<bf16_t>(st, p.wo), rows, d.H, d.qd, y, d.H, r, s));
     PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, row_ext, rows, d.H, d.eps, s));
     GemmEpilogue g = split;
     g.rstd = rstd;
-    PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, g, s));
+    PROF(st, HYP_K_GEMM_GATEUP, mfma_gemm(EPI_SWIGLU, HYP_K_GEMM_GATEUP, y, at<bf16_t>(st, p.wgu), rows, 2 * d.I, d.H, m, d.I, g, s));
     if (!last) {
       r.gain = at<bf16_t>(st, L.layers[l + 1].g1);
-      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_RESID, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, y, d.H, r, s));
+      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_RESID, HYP_K_GEMM_DOWN, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, y, d.H, r, s));
       PROF(st, HYP_K_ADD_NORM, mfma_rstd(ssq_part, rstd, row_ext, rows, d.H, d.eps, s));
     } else {
-      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, split, s));
+      PROF(st, HYP_K_GEMM_DOWN, mfma_gemm(EPI_STORE, HYP_K_GEMM_DOWN, m, at<bf16_t>(st, p.wd), rows, d.H, d.I, delta, d.H, split, s));
       PROF(st, HYP_K_ADD_NORM, mfma_prefill_end(xres, delta, (bf16_t *)hidden_out, row_ext, rows, d.H, s));
     }
   }
@@ -444,27 +444,27 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const DecScratch &sc
     a.ssq_in = ssq; a.n_ssq = d.H / (l == 0 ? 64 : 32 * L.fbw_d);  // written by the opening kernel / the previous down GEMM
     a.lens = at<int>(st, L.lens); a.cos_tab = at<float>(st, L.cos_tab); a.sin_tab = at<float>(st, L.sin_tab);
     a.qdec = sc.qdec; a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
-    PROF(st, HYP_K_GEMV_QKV, mfma_dec_gemv(DEC_QKV, a, s));
+    PROF(st, HYP_K_GEMV_QKV, mfma_dec_gemv(DEC_QKV, HYP_K_GEMV_QKV, a, s));
     PROF(st, HYP_K_ATTN_DECODE, mfma_attn_decode(a.qdec, Kc, Vc, geom, a.lens, sc.attn_part,
                                                  attn, d.nq, d.nkv, st->batch,
                                                  L.max_chunks, L.chunk_keys, s));
     DecGemv o = base;
     o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.ksplit = L.ks_o; o.max_ksplit = 2 * o.ksplit; o.fbw = L.fbw_o;
     o.gain = at<bf16_t>(st, p.g2); o.y_out = y; o.ssq_out = ssq;
-    PROF(st, HYP_K_GEMV_O, mfma_dec_gemv(DEC_RESID, o, s));
+    PROF(st, HYP_K_GEMV_O, mfma_dec_gemv(DEC_RESID, HYP_K_GEMV_O, o, s));
     DecGemv g = base;
     g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.ksplit = L.ks_gu; g.max_ksplit = 2 * g.ksplit;
     g.ssq_in = ssq; g.n_ssq = d.H / (32 * L.fbw_o); g.m_out = m; g.I = d.I;
-    PROF(st, HYP_K_GEMV_GATEUP, mfma_dec_gemv(DEC_SWIGLU, g, s));
+    PROF(st, HYP_K_GEMV_GATEUP, mfma_dec_gemv(DEC_SWIGLU, HYP_K_GEMV_GATEUP, g, s));
     DecGemv w = base;
     w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.ksplit = L.ks_d; w.max_ksplit = 2 * w.ksplit; w.fbw = L.fbw_d;
     if (l + 1 < st->n_layers) {
       w.gain = at<bf16_t>(st, L.layers[l + 1].g1); w.y_out = y; w.ssq_out = ssq;
-      PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_RESID, w, s));
+      PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_RESID, HYP_K_GEMV_DOWN, w, s));
     } else {
       w.hidden_out = (bf16_t *)hidden_out;
       w.lens_advance = at<int>(st, L.lens);
-      PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_FINAL, w, s));
+      PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_FINAL, HYP_K_GEMV_DOWN, w, s));
     }
   }
   return HYP_OK;

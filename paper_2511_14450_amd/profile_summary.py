@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Turn rocprofv3 CSV output of `bench.py` into the short text summaries kept under profiles/.
 
-  kernel stats :  python profile_summary.py stats  <dir>/<name>_kernel_stats.csv
-  HBM traffic  :  python profile_summary.py traffic <fetch>_counter_collection.csv <write>_counter_collection.csv
-                  [--json profiles/traffic_c3_stage10.json --workload c3_stage10]
-  MFMA / waits :  python profile_summary.py counters <dir>/<name>_counter_collection.csv
+  kernel stats :  python -m paper_2511_14450_amd.profile_summary stats  <dir>/<name>_kernel_stats.csv
+  HBM traffic  :  python -m paper_2511_14450_amd.profile_summary traffic <fetch>_counter_collection.csv <write>_counter_collection.csv
+                  [--json profiles/traffic_c5_long.json --workload c5_long]
+  MFMA / waits :  python -m paper_2511_14450_amd.profile_summary counters <dir>/<name>_counter_collection.csv
 
 FETCH_SIZE / WRITE_SIZE are reported by rocprofv3 in KiB per dispatch; both are scaled by
 what the same counter reads for the 256 MiB device copy that `bench.py --traffic-calibration`
@@ -16,29 +16,18 @@ import argparse
 import collections
 import csv
 import json
+import pathlib
 import re
 import sys
 
-CLASS_OF = [  # (regex on the kernel name, grid-x test, class)
-    (r"k_gemm<2>", "gemm_qkv"), (r"k_gemm<1>", "gemm_gateup"), (r"k_attn_prefill", "attn_prefill"),
-    # in the one-block counter run the O projection is the only residual-epilogue GEMM and the
-    # down projection (last block of the stage) the only plain-epilogue one
-    (r"k_gemm<3>", "gemm_o"), (r"k_gemm<0>", "gemm_down"), (r"k_rstd", "add_norm"),
-    (r"k_attn_decode_merge", "attn_decode_merge"), (r"k_attn_decode", "attn_decode"),
-    (r"k_dec_gemv<0, \d>", "gemv_qkv"), (r"k_dec_gemv<1, \d>", "gemv_gateup"), (r"k_add_norm", "add_norm"),
-    # residual decode GEMMs: 32-row workgroups are the O projection, 64-row ones the down projection
-    # (on the bench shapes; the grid table below covers a build where both use 64 rows)
-    (r"k_dec_gemv<2, 1>", "gemv_o"), (r"k_dec_gemv<3, 1>", "gemv_o"),
-    (r"k_dec_begin", "dec_begin"),
-]
-
-
-# kernels shared by two classes, told apart by their launch size on the c3 workload
-# (total work-items): the decode O / down projections differ in ksplit
-NAME_BY_GRID = {
-    "k_dec_gemv<2, 2>/grid102400": "gemv_down", "k_dec_gemv<3, 2>/grid102400": "gemv_down",
-    "k_dec_gemv<2, 2>/grid40960": "gemv_o",
-}
+# kernel class, as bench.py and hyp_stage.h name it, of every kernel of the MFMA path.  The GEMM
+# kernels carry their class as their last template argument (a hyp_kernel_class_t), so the O and
+# down projections, which share an epilogue, have different names in a trace.
+CLASS_BY_ID = {1: "gemm_qkv", 3: "gemm_o", 4: "gemm_gateup", 5: "gemm_down",
+               6: "gemv_qkv", 9: "gemv_o", 10: "gemv_gateup", 12: "gemv_down"}
+CLASS_BY_NAME = [(r"k_attn_prefill", "attn_prefill"), (r"k_attn_decode_merge", "attn_decode_merge"),
+                 (r"k_attn_decode", "attn_decode"), (r"k_rstd", "add_norm"), (r"k_add_norm", "add_norm"),
+                 (r"k_dec_begin", "dec_begin")]
 
 
 def short(name: str) -> str:
@@ -47,15 +36,13 @@ def short(name: str) -> str:
 
 
 def classify(row) -> str:
-    """Kernel class as bench.py names it; the two plain-epilogue GEMMs and the two residual
-    decode GEMMs share a kernel and are told apart by their grid."""
     n = short(row["Kernel_Name"])
-    grid = row.get("Grid_Size") or (row.get("Grid_Size_X", "") + "x" + row.get("Grid_Size_Y", ""))
-    for pat, cls in CLASS_OF:
+    m = re.match(r"k_(gemm|dec_gemv)<.*?(\d+)>$", n)
+    if m:
+        return CLASS_BY_ID.get(int(m.group(2)), n)
+    for pat, cls in CLASS_BY_NAME:
         if re.search(pat, n):
             return cls
-    if n.startswith("k_dec_gemv<2") or n.startswith("k_dec_gemv<3"):
-        return n + f"/grid{grid}"
     return n
 
 
@@ -97,13 +84,13 @@ def traffic(fetch_csv, write_csv, out_json, workload):
     for cls in sorted(set(f) | set(w)):
         if not cls.startswith(("gemm", "gemv", "attn", "k_gemm", "k_dec", "add_norm", "dec_")):
             continue
-        cls_out = NAME_BY_GRID.get(cls, cls)
+        cls_out = cls
         fb = sum(f.get(cls, [0])) / max(len(f.get(cls, [1])), 1) * fscale * 1024
         wb = sum(w.get(cls, [0])) / max(len(w.get(cls, [1])), 1) * wscale * 1024
         print(f"{cls_out:36s} {len(f.get(cls, [])):8d} {fb / 2**20:10.1f} {wb / 2**20:10.1f}")
         result[cls_out] = fb + wb
     if out_json:
-        sys.path.insert(0, ".")
+        sys.path.insert(0, str(pathlib.Path(__file__).resolve().parents[1]))
         import bench
         json.dump({"workload": workload, "sources_sha256": bench.kernel_sources_digest(),
                    "unit": "bytes (FETCH_SIZE + WRITE_SIZE, scaled by the copy calibration)",
@@ -133,7 +120,7 @@ if __name__ == "__main__":
     ap.add_argument("mode", choices=["stats", "traffic", "counters"])
     ap.add_argument("files", nargs="+")
     ap.add_argument("--json")
-    ap.add_argument("--workload", default="c3_stage10")
+    ap.add_argument("--workload", default="c5_long")
     a = ap.parse_args()
     if a.mode == "stats":
         stats(a.files[0])

@@ -199,12 +199,18 @@ def run_whole_model(model: str, split: Sequence[int], prompt: int, generate: int
     return res
 
 
-def measure_block_costs(model: str, prompt: int, generate: int, batch: int = 1, seed: int = 251114450):
+def _model_spec(model):
+    """A name from MODELS, or a dict with the same keys (blocks, hidden, n_q_heads, n_kv_heads,
+    head_dim, ffn_dim) for any other bf16 model."""
+    return MODELS[model] if isinstance(model, str) else dict(model)
+
+
+def measure_block_costs(model, prompt: int, generate: int, batch: int = 1, seed: int = 251114450):
     """What Algorithm 1 needs to know about a block, measured on this device: f = the
     seconds one block spends on a request of the given shape (prefill + every decode
     step; all blocks of a model have one shape, so one block is measured), m = the bytes
     a block adds to a stage (repacked weights + its share of the KV cache)."""
-    m = MODELS[model]
+    m = _model_spec(model)
     shape = _Shape(m)
     chain = StageChain(shape, [0, 1], _synthetic_layer(shape, seed), batch, prompt + generate + 1, batch * prompt)
     gen = torch.Generator(device="cuda")
@@ -227,11 +233,11 @@ def measure_block_costs(model: str, prompt: int, generate: int, batch: int = 1, 
     return seconds, float(bytes_per_block)
 
 
-def plan_split(model: str, tiers: Sequence[Sequence[float]], prompt: int, generate: int, eps: float, batch: int = 1):
+def plan_split(model, tiers: Sequence[Sequence[float]], prompt: int, generate: int, eps: float, batch: int = 1):
     """HypSplit-DP (Sec. IV-A) on measured block costs.  tiers = [(capacity, memory GB), ...]
     in the order the pipeline visits them; capacities are relative (Table I lists TOPS):
     the largest stands for this device, f_i / C_j is then the time of block i on tier j."""
-    n = MODELS[model]["blocks"]
+    n = _model_spec(model)["blocks"]
     f1, m1 = measure_block_costs(model, prompt, generate, batch)
     cap_ref = max(float(c) for c, _ in tiers)
     C = [float(c) / cap_ref for c, _ in tiers]
@@ -239,7 +245,7 @@ def plan_split(model: str, tiers: Sequence[Sequence[float]], prompt: int, genera
     t0 = time.perf_counter()
     p, tau = binding.hypsplit_dp([f1] * n, [m1] * n, C, M, eps)
     dt = time.perf_counter() - t0
-    plan = {"model": model, "blocks": n, "tiers": [[float(c), float(g)] for c, g in tiers], "eps": eps,
+    plan = {"model": model if isinstance(model, str) else "custom", "blocks": n, "tiers": [[float(c), float(g)] for c, g in tiers], "eps": eps,
             "f_seconds_per_block": f1, "m_bytes_per_block": m1, "p": p, "tau_seconds": tau,
             "hypsplit_dp_seconds": dt}
     if p is not None:

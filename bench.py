@@ -122,7 +122,7 @@ def cpu_baseline(wl, prompt=2048, decode=32):
     }
 
 
-def run_workload(wl, steps, warmup, no_graph=False, traffic_calibration=False, profile_stride=16):
+def run_workload(wl, steps, warmup, no_graph=False, traffic_calibration=False, profile_stride=16, paged=False):
     """Time `steps` steps of one workload (after `warmup` untimed ones), then one more pass with events
     around the launches of every kernel class (all prefill launches; every `profile_stride`-th decode step)."""
     import torch
@@ -132,10 +132,15 @@ def run_workload(wl, steps, warmup, no_graph=False, traffic_calibration=False, p
     lens = wl.lengths()
     B, T = len(lens), sum(lens)
     n_dec = wl.decode_steps
-    cfg = hyp.stage_config(shape, B, max(lens) + n_dec, T, flags=binding.HYP_FLAG_NO_GRAPH if no_graph else 0)
+    flags = (binding.HYP_FLAG_NO_GRAPH if no_graph else 0) | (binding.HYP_FLAG_PAGED_KV if paged else 0)
+    cfg = hyp.stage_config(shape, B, max(lens) + n_dec, T, flags=flags)
     layers = device_weights(shape, wl.n_layers, wl.seed)
     stage = hyp.stage_create(cfg, 0, wl.n_layers, layers)
     del layers
+    if paged:  # the cache's 128-key pages handed to the requests in a seeded shuffled order
+        ppr = -(-((max(lens) + n_dec + 63) // 64 * 64) // binding.HYP_KV_PAGE_KEYS)
+        perm = np.random.Generator(np.random.Philox(key=[wl.seed, 11])).permutation(B * ppr)
+        stage.set_page_table([[int(v) for v in perm[r * ppr:(r + 1) * ppr]] for r in range(B)])
     torch.cuda.empty_cache()
     assert stage.uses_mfma(), "the bench workloads must run on the MFMA path"
 
@@ -232,7 +237,7 @@ def run_workload(wl, steps, warmup, no_graph=False, traffic_calibration=False, p
     out = {
         "value": tokens_per_step / (ms_per_step * 1e-3),
         "ms_per_step": ms_per_step,
-        "config": {"workload": wl.name, "layers": wl.n_layers, "batch": B, "prefill_tokens": T,
+        "config": {"workload": wl.name + (" (paged KV cache, shuffled 128-key pages)" if paged else ""), "layers": wl.n_layers, "batch": B, "prefill_tokens": T,
                    "decode_steps": n_dec, "hidden": H, "ffn": I, "q_heads": shape.n_q_heads,
                    "kv_heads": shape.n_kv_heads},
         "prefill_tokens_per_s": T / (pre * 1e-3),
@@ -335,6 +340,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the block count (counter runs on a shorter stage)")
     ap.add_argument("--decode-steps", type=int, default=-1, help="override the number of decode steps")
     ap.add_argument("--no-graph", action="store_true", help="launch decode kernels one by one (for counter runs)")
+    ap.add_argument("--paged", action="store_true", help="keep the KV cache in 128-key pages behind a shuffled page table")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one 256 MiB device copy, the known-size reference for FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -354,7 +360,8 @@ def main():
     if overridden:
         wl = dataclasses.replace(wl, n_layers=args.layers if args.layers > 0 else wl.n_layers,
                                  decode_steps=args.decode_steps if args.decode_steps >= 0 else wl.decode_steps)
-    r = run_workload(wl, args.steps, args.warmup, no_graph=args.no_graph, traffic_calibration=args.traffic_calibration)
+    r = run_workload(wl, args.steps, args.warmup, no_graph=args.no_graph, traffic_calibration=args.traffic_calibration,
+                     paged=args.paged)
     if overridden:
         r["config"]["workload"] += " (overridden)"
     out = {
@@ -383,6 +390,7 @@ def main():
             if args.workload != DEFAULT_WORKLOAD:
                 others.remove(DEFAULT_WORKLOAD)  # the 20-block stage only as the headline
             out["other_configs"] = [brief(run_workload(synth.WORKLOADS[k], 2, 1)) for k in others]
+            out["other_configs"].append(brief(run_workload(synth.WORKLOADS["c4_decode_heavy"], 2, 1, paged=True)))
             out["other_configs"].append(prefill_only_line("c2_layer_prefill"))
     if not args.no_cpu_baseline:
         progress("timing the CPU oracle on its sample")

@@ -63,6 +63,10 @@ typedef enum { HYP_F32 = 0, HYP_BF16 = 1 } hyp_dtype_t;
 /* hyp_stage_config_t.flags */
 #define HYP_FLAG_NO_GRAPH 2u      /* launch the decode-step kernels one by one instead of replaying \
                                      a recorded HIP graph                                 */
+#define HYP_FLAG_PAGED_KV 4u      /* keep the KV cache in pages of HYP_KV_PAGE_KEYS keys addressed through a \
+                                     page table (stage_set_page_table) instead of one slab per request; \
+                                     stages on the MFMA kernels only                                   */
+#define HYP_KV_PAGE_KEYS 128
 #define HYP_FLAG_PLAIN_KERNELS 1u /* diagnostics: run the shape-generic HIP kernels even \
                                      where the MFMA kernels apply                        */
 
@@ -79,7 +83,8 @@ typedef struct {
   int32_t max_seq;      /* per-request capacity: prompt + generated tokens    */
   int64_t max_prefill_tokens; /* bound on sum(seq_lens) of one stage_prefill   */
   uint32_t flags;
-  uint32_t reserved;    /* must be 0                                          */
+  uint32_t kv_pool_pages; /* HYP_FLAG_PAGED_KV: pages in the pool of every block; 0 = enough for
+                             max_batch requests of max_seq keys.  Must be 0 without the flag.   */
 } hyp_stage_config_t;
 
 /* Weights of one block: device pointers, row-major [out_features, in_features]
@@ -111,8 +116,8 @@ HYP_API size_t stage_workspace_bytes(const hyp_stage_config_t *cfg, int32_t l_st
  * The weights are copied into the workspace in the library's layout and the
  * call returns only after that copy has finished, so the caller may release the
  * original weight tensors afterwards.
- * Errors: HYP_EINVAL (null pointer, l_start < 0, l_start >= l_end, bad dtype,
- * reserved != 0), HYP_ESHAPE (non-positive size, n_q_heads % n_kv_heads != 0, odd
+ * Errors: HYP_EINVAL (null pointer, l_start < 0, l_start >= l_end, bad dtype, unknown
+ * flag, kv_pool_pages without HYP_FLAG_PAGED_KV), HYP_ESHAPE (non-positive size, n_q_heads % n_kv_heads != 0, odd
  * head_dim), HYP_ENOMEM (workspace too small or misaligned), HYP_EDEVICE. */
 HYP_API hyp_status_t stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int32_t l_end,
                           const hyp_layer_weights_t *layers, void *workspace,
@@ -156,6 +161,27 @@ HYP_API hyp_status_t stage_decode_step(hyp_stage_t *stage, const void *hidden_in
  * HYP_ECAPACITY when one step's temporaries exceed the array (the Phi-3-medium-shaped and
  * Llama3-8B-shaped blocks at up to 32 requests fit); nothing is changed then. */
 HYP_API hyp_status_t stage_decode_step_noalloc(hyp_stage_t *stage, const void *hidden_in, void *hidden_out);
+
+/* Paged KV cache ("weights and associated caches" stay resident on the node, Sec. V-D; with
+ * pages a request only occupies the keys it holds, so more requests fit one node's memory).
+ * A stage created with HYP_FLAG_PAGED_KV stores keys and values in a pool of pages of
+ * HYP_KV_PAGE_KEYS keys per block of the stage; this call says which pages the request slots use:
+ *   table  host, [n_requests][pages_per_request]: table[r][i] is the pool page (0 <=
+ *          page < kv_pool_pages, the same in every block of the stage) that holds keys
+ *          [128 i, 128 i + 128) of request slot r, or -1 for none; no page may appear twice.
+ *          Slots >= n_requests and columns >= pages_per_request get no page.  Copied before
+ *          the call returns (the call waits for the stage's stream).
+ * It applies to the prefill and decode calls that follow; pages that already hold cached keys
+ * of a resident request must keep their place (HYP_ESTATE otherwise).  Without this call,
+ * slot r owns pages r * ceil(max_seq / 128) ... when the pool has max_batch * ceil(max_seq /
+ * 128) pages; a smaller pool starts with no pages assigned.  stage_prefill and
+ * stage_decode_step return HYP_ECAPACITY, changing nothing, when a request has no page for a
+ * key they would write (a prompt is written up to the next multiple of 64 keys).
+ * Errors: HYP_EINVAL (null, counts < 1, page outside the pool or assigned twice),
+ * HYP_ECAPACITY (n_requests > max_batch, a page beyond max_seq), HYP_ESTATE (stage without
+ * the flag, or see above), HYP_EDEVICE. */
+HYP_API hyp_status_t stage_set_page_table(hyp_stage_t *stage, const int32_t *table, int32_t n_requests,
+                                          int32_t pages_per_request);
 
 /* Copy the cached keys (post-RoPE) and values of one request and one block of
  * the stage (layer in [0, l_end - l_start)) to k_out / v_out, device,

@@ -8,7 +8,7 @@ has not been built (python -m paper_2511_14450_amd.build).
 from .binding import (  # noqa: F401
     HypError, LayerWeights, Stage, StageConfig, library_path, load_library,
     stage_context_len, stage_create, stage_decode_step, stage_decode_step_noalloc, stage_destroy, stage_export_kv,
-    stage_last_error, stage_prefill, stage_profile, stage_profile_read, stage_uses_mfma,
+    stage_last_error, stage_prefill, stage_set_page_table, stage_profile, stage_profile_read, stage_uses_mfma,
     stage_workspace_bytes, KERNEL_CLASSES, stage_config, hyp_measure_mfma_ceiling,
     hyp_measure_hbm_read_ceiling, hypsplit_dp, hypsched_rt, hypsched_simulate,
 )

@@ -19,9 +19,11 @@ STATUS_NAMES = ["HYP_OK", "HYP_EINVAL", "HYP_ESHAPE", "HYP_ECAPACITY", "HYP_ESTA
 HYP_F32, HYP_BF16 = 0, 1
 HYP_FLAG_PLAIN_KERNELS = 1
 HYP_FLAG_NO_GRAPH = 2
+HYP_FLAG_PAGED_KV = 4
+HYP_KV_PAGE_KEYS = 128
 
 EXPORTS = ("stage_workspace_bytes", "stage_create", "stage_prefill", "stage_decode_step", "stage_decode_step_noalloc",
-           "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",
+           "stage_set_page_table", "stage_export_kv", "stage_context_len", "stage_destroy", "stage_last_error",
            "stage_uses_mfma", "stage_profile", "stage_profile_read",
            "hyp_measure_mfma_ceiling", "hyp_measure_hbm_read_ceiling")
 EXPORTS_PLAN = ("hypsplit_dp", "hypsched_rt", "hypsched_simulate")  # include/hyp_plan.h
@@ -41,7 +43,7 @@ class StageConfig(C.Structure):
                 ("head_dim", C.c_int32), ("ffn_dim", C.c_int32), ("rms_eps", C.c_float),
                 ("rope_base", C.c_float), ("dtype", C.c_int32), ("max_batch", C.c_int32),
                 ("max_seq", C.c_int32), ("max_prefill_tokens", C.c_int64), ("flags", C.c_uint32),
-                ("reserved", C.c_uint32)]
+                ("kv_pool_pages", C.c_uint32)]
 
 
 _WEIGHT_FIELDS = ("attn_norm_g", "wq", "wk", "wv", "wo", "ffn_norm_g", "w_gate", "w_up", "w_down")
@@ -51,14 +53,15 @@ class LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
 
 
-def stage_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, flags: int = 0) -> StageConfig:
+def stage_config(shape, max_batch: int, max_seq: int, max_prefill_tokens: int, flags: int = 0,
+                 kv_pool_pages: int = 0) -> StageConfig:
     """StageConfig from any object with the block-shape attributes (hidden, n_q_heads,
     n_kv_heads, head_dim, ffn_dim, rms_eps, rope_base, dtype in {"f32", "bf16"})."""
     return StageConfig(hidden=shape.hidden, n_q_heads=shape.n_q_heads, n_kv_heads=shape.n_kv_heads,
                        head_dim=shape.head_dim, ffn_dim=shape.ffn_dim, rms_eps=shape.rms_eps,
                        rope_base=shape.rope_base, dtype=HYP_BF16 if shape.dtype == "bf16" else HYP_F32,
                        max_batch=max_batch, max_seq=max_seq, max_prefill_tokens=max_prefill_tokens,
-                       flags=flags, reserved=0)
+                       flags=flags, kv_pool_pages=kv_pool_pages)
 
 
 def library_path() -> pathlib.Path:
@@ -86,6 +89,8 @@ def load_library() -> C.CDLL:
     lib.stage_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.stage_decode_step_noalloc.restype = C.c_int
     lib.stage_decode_step_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.stage_set_page_table.restype = C.c_int
+    lib.stage_set_page_table.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32, C.c_int32]
     lib.stage_export_kv.restype = C.c_int
     lib.stage_export_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.stage_context_len.restype = C.c_int
@@ -148,6 +153,9 @@ class Stage:
 
     def decode_step_noalloc(self, hidden_in, hidden_out):
         return stage_decode_step_noalloc(self, hidden_in, hidden_out)
+
+    def set_page_table(self, table):
+        return stage_set_page_table(self, table)
 
     def export_kv(self, layer, request):
         return stage_export_kv(self, layer, request)
@@ -245,6 +253,13 @@ def _validate_io(stage: Stage, a: torch.Tensor, b: torch.Tensor, rows: Optional[
             raise ValueError(f"hidden states must be contiguous {dt} device tensors [rows, {stage.cfg.hidden}]")
     if a.shape != b.shape or (rows is not None and a.shape[0] != rows):
         raise ValueError("hidden_in / hidden_out row count does not match the request lengths")
+
+
+def stage_set_page_table(stage: Stage, table: Sequence[Sequence[int]]) -> None:
+    """table[r][i] = pool page of keys [128 i, 128 i + 128) of request slot r, -1 for none (rows of equal length)."""
+    n, ppr = len(table), len(table[0]) if len(table) else 0
+    flat = (C.c_int32 * max(n * ppr, 1))(*[int(v) for row in table for v in row])
+    _check(load_library().stage_set_page_table(stage.handle, flat, n, ppr), stage.handle)
 
 
 def stage_context_len(stage: Stage, request: int) -> int:

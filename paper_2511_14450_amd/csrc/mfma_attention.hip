@@ -72,21 +72,29 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  auto issue = [&](int st, int buf) {
+  // A stage is the pair of key blocks 2 st, 2 st + 1: 16 KiB contiguous in either cache layout
+  // (the block count of a request is even and a page holds four blocks).  Its offset is uniform
+  // over the workgroup and, with a paged cache, costs a table lookup: it is formed one stage
+  // before the loads that use it are issued.
+  auto stage_off = [&](int st) { return geom.off(tile.req, kvh, min(st * 2, geom.key_blocks - 2)); };
+  auto issue = [&](size_t off, int buf) {
     // 32 tiles of 1 KiB: [key block 0: 8 K, 8 V][key block 1: 8 K, 8 V]; the second
     // block of the last stage may lie past the tile's need but is inside the cache
     for (int t = wave; t < 32; t += nw) {
-      int kb = min(st * 2 + (t >> 4), geom.key_blocks - 1);
-      const bf16_t *src = ((t & 8) ? Vc : Kc) + geom.off(tile.req, kvh, kb) + (size_t)(t & 7) * kTileElems + lane * 8;
+      const bf16_t *src = ((t & 8) ? Vc : Kc) + off + (size_t)(t >> 4) * (32 * 128) + (size_t)(t & 7) * kTileElems + lane * 8;
       __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvStageBytes + t * 1024), 16, 0, 0);
     }
   };
-  issue(0, 0);
+  issue(stage_off(0), 0);
+  size_t off_next = stage_off(1);
   for (int st = 0; st < n_st; ++st) {
     const int buf = st & 1;
     __builtin_amdgcn_s_waitcnt(0x0070);  // my loads landed, my LDS reads of the previous stage done
     __syncthreads();
-    if (st + 1 < n_st) issue(st + 1, buf ^ 1);
+    if (st + 1 < n_st) {
+      issue(off_next, buf ^ 1);
+      off_next = stage_off(st + 2);
+    }
     const int kb0 = st * 2;
     if (kb0 > qblk) continue;  // this wave's rows end before the stage's keys start (barrier is at the loop top)
     const char *base = lds + buf * kKvStageBytes + lane * 16;

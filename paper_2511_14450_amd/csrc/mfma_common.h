@@ -59,13 +59,24 @@ __host__ __device__ inline int vtile_slot_of_key(int key_in_block, int *m, int *
   return ((w >> 3) << 2) + (w & 3);
 }
 
-// Geometry of the caches for one (layer): [request][kv_head][key_block][8 KiB]
+// Geometry of the caches of one layer.  Contiguous form: [request][kv_head][key_block][8 KiB].
+// Paged form (page_table != nullptr): the cache is a pool of pages of kPageKeys keys,
+// [page][kv_head][kPageBlocks][8 KiB], and page_table[request * pages_per_req + i] names the page
+// that holds keys [kPageKeys * i, kPageKeys * (i + 1)) of that request.  Either way a 32-key block
+// of one KV head is 8 KiB contiguous and a page keeps a head's blocks together, so the kernels
+// stream the same tiles; only the block address differs.
+constexpr int kPageKeys = 128, kPageBlocks = kPageKeys / 32;
 struct CacheGeom {
   int nkv;
   int key_blocks;  // ceil(max_seq / 32)
+  const int *page_table;
+  int pages_per_req;
   __host__ __device__ size_t block_elems() const { return 32 * 128; }
-  __host__ __device__ size_t head_elems() const { return (size_t)key_blocks * 32 * 128; }
   __host__ __device__ size_t off(int req, int kvh, int kb) const {
+    if (page_table) {
+      const int page = page_table[req * pages_per_req + kb / kPageBlocks];
+      return (((size_t)page * nkv + kvh) * kPageBlocks + kb % kPageBlocks) * (32 * 128);
+    }
     return (((size_t)req * nkv + kvh) * key_blocks + kb) * (32 * 128);
   }
 };

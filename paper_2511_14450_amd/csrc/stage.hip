@@ -75,6 +75,9 @@ struct Layout {
   int ks_qkv = 1, ks_o = 1, ks_gu = 1, ks_d = 1;
   int fbw_o = 2, fbw_d = 2;  // 32-row blocks per workgroup of the two residual decode GEMMs
   size_t partial_bytes = 0, attn_part_bytes = 0, counters_bytes = 0;
+  // paged KV cache (HYP_FLAG_PAGED_KV): pages per layer of the pool, table entries per request
+  size_t page_table = 0;
+  int pool_pages = 0, pages_per_req = 0;
   size_t total = 0;
 };
 
@@ -114,7 +117,8 @@ hyp_status_t check_config(const hyp_stage_config_t *c, int32_t l_start, int32_t 
   if (!c) { err = "config is NULL"; return HYP_EINVAL; }
   if (l_start < 0 || l_start >= l_end) { err = "need 0 <= l_start < l_end"; return HYP_EINVAL; }
   if (c->dtype != HYP_F32 && c->dtype != HYP_BF16) { err = "dtype must be HYP_F32 or HYP_BF16"; return HYP_EINVAL; }
-  if (c->reserved != 0) { err = "reserved must be 0"; return HYP_EINVAL; }
+  if (c->kv_pool_pages != 0 && !(c->flags & HYP_FLAG_PAGED_KV)) { err = "kv_pool_pages must be 0 unless HYP_FLAG_PAGED_KV is set"; return HYP_EINVAL; }
+  if (c->flags & ~(HYP_FLAG_PLAIN_KERNELS | HYP_FLAG_NO_GRAPH | HYP_FLAG_PAGED_KV)) { err = "unknown flag"; return HYP_EINVAL; }
   if (c->hidden < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 2 || c->ffn_dim < 1 ||
       c->max_batch < 1 || c->max_seq < 1 || c->max_prefill_tokens < 1) {
     err = "sizes must be positive"; return HYP_ESHAPE;
@@ -127,6 +131,11 @@ hyp_status_t check_config(const hyp_stage_config_t *c, int32_t l_start, int32_t 
     err = "max_prefill_tokens exceeds max_batch * max_seq"; return HYP_ESHAPE;
   }
   if (c->max_prefill_tokens > (int64_t)1 << 30) { err = "max_prefill_tokens too large"; return HYP_ESHAPE; }
+  if ((c->flags & HYP_FLAG_PAGED_KV) && !mfma_applies(*c)) {
+    err = "HYP_FLAG_PAGED_KV needs a stage that runs the MFMA kernels (bf16, head_dim 128, widths in multiples of 256)";
+    return HYP_ESHAPE;
+  }
+  if ((uint64_t)c->kv_pool_pages > (uint64_t)1 << 24) { err = "kv_pool_pages too large"; return HYP_ESHAPE; }
   return HYP_OK;
 }
 
@@ -152,7 +161,13 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     if (L.rows_cap < 64) L.rows_cap = 64;
     R = L.rows_cap;
     L.key_blocks = round_up(c.max_seq, 64) / 32;
-    L.kv_layer_stride = align_up(es * (size_t)c.max_batch * c.n_kv_heads * L.key_blocks * 32 * 128);
+    if (c.flags & HYP_FLAG_PAGED_KV) {
+      L.pages_per_req = (L.key_blocks + kPageBlocks - 1) / kPageBlocks;
+      L.pool_pages = c.kv_pool_pages ? (int)c.kv_pool_pages : c.max_batch * L.pages_per_req;
+      L.kv_layer_stride = align_up(es * (size_t)L.pool_pages * c.n_kv_heads * kPageBlocks * 32 * 128);
+    } else {
+      L.kv_layer_stride = align_up(es * (size_t)c.max_batch * c.n_kv_heads * L.key_blocks * 32 * 128);
+    }
     L.kv_bytes = L.kv_layer_stride * n_layers;
     L.Kc = take(L.kv_bytes);
     L.Vc = take(L.kv_bytes);
@@ -194,6 +209,7 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.gemm_counters = take(sizeof(unsigned) * kGemmSplitMaxTiles);  // zeroed together with `counters`
     L.ssq = take(sizeof(float) * 32 * (H / 32));
     L.gemm_ws = take(mfma_gemm_split_ws_bytes());
+    if (L.pages_per_req) L.page_table = take(sizeof(int) * (size_t)c.max_batch * L.pages_per_req);
     L.total = off;
     return;
   }
@@ -233,6 +249,7 @@ struct hyp_stage {
   hipEvent_t upload_done;
   bool upload_pending;
   std::vector<int> lens;  // host mirror of the cached lengths
+  std::vector<int> pages;  // paged cache: host mirror of the page table [max_batch][pages_per_req], -1 = none
   // optional per-kernel-class timing with HIP events on the stage's stream
   struct ProfSlot { hipEvent_t a, b; int cls; };
   std::vector<ProfSlot> prof;
@@ -364,6 +381,8 @@ CacheGeom cache_geom(const hyp_stage *st) {
   CacheGeom g;
   g.nkv = st->dm.nkv;
   g.key_blocks = st->L.key_blocks;
+  g.pages_per_req = st->L.pages_per_req;
+  g.page_table = st->L.pages_per_req ? reinterpret_cast<const int *>(st->ws + st->L.page_table) : nullptr;
   return g;
 }
 
@@ -547,6 +566,21 @@ hyp_status_t run_plain(hyp_stage *st, const void *hidden_in, void *hidden_out, i
   return HYP_OK;
 }
 
+// paged cache: the first key of request b in [0, n_keys) that has no page, or -1
+int first_key_without_page(const hyp_stage *st, int b, int n_keys) {
+  const int ppr = st->L.pages_per_req;
+  for (int i = 0; i * kPageKeys < n_keys; ++i)
+    if (i >= ppr || st->pages[(size_t)b * ppr + i] < 0) return i * kPageKeys;
+  return -1;
+}
+
+hyp_status_t upload_page_table(hyp_stage *st) {
+  HIP_TRY(st, hipMemcpyAsync(st->ws + st->L.page_table, st->pages.data(), sizeof(int) * st->pages.size(),
+                             hipMemcpyHostToDevice, st->stream));
+  HIP_TRY(st, hipStreamSynchronize(st->stream));  // the host mirror may change right after
+  return HYP_OK;
+}
+
 hyp_status_t wait_upload(hyp_stage *st) {
   if (st->upload_pending) {
     HIP_TRY(st, hipEventSynchronize(st->upload_done));
@@ -660,6 +694,14 @@ hyp_status_t do_stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int
       }
     }
     rc = pack_weights_mfma(st, layers);
+    if (rc == HYP_OK && st->L.pages_per_req) {
+      // until stage_set_page_table says otherwise: request r owns pages r * ppr .. if the pool has that many
+      const int ppr = st->L.pages_per_req;
+      st->pages.assign((size_t)cfg->max_batch * ppr, -1);
+      if (st->L.pool_pages >= cfg->max_batch * ppr)
+        for (size_t i = 0; i < st->pages.size(); ++i) st->pages[i] = (int)i;
+      rc = upload_page_table(st);
+    }
   } else {
     rc = copy_weights(st, layers);
   }
@@ -708,6 +750,12 @@ hyp_status_t do_stage_prefill(hyp_stage_t *st, const void *hidden_in, const int3
     total += seq_lens[b];
   }
   if (total > st->cfg.max_prefill_tokens) return fail(st, HYP_ECAPACITY, "sum(seq_lens) exceeds max_prefill_tokens");
+  if (st->L.pages_per_req)
+    for (int b = 0; b < batch; ++b) {  // the padded rows of a prompt are written to the cache as well
+      int k = first_key_without_page(st, b, round_up(seq_lens[b], 64));
+      if (k >= 0)
+        return fail(st, HYP_ECAPACITY, "request " + std::to_string(b) + " has no cache page for key " + std::to_string(k));
+    }
   int rows = (int)total;
 
   hyp_status_t rc = wait_upload(st);
@@ -780,6 +828,12 @@ hyp_status_t check_decode_args(hyp_stage *st, const void *hidden_in, void *hidde
   for (int b = 0; b < st->batch; ++b)
     if (st->lens[b] >= st->cfg.max_seq)
       return fail(st, HYP_ECAPACITY, "request " + std::to_string(b) + " already holds max_seq tokens");
+  if (st->L.pages_per_req)
+    for (int b = 0; b < st->batch; ++b) {
+      const int i = st->lens[b] / kPageKeys;
+      if (st->pages[(size_t)b * st->L.pages_per_req + i] < 0)
+        return fail(st, HYP_ECAPACITY, "request " + std::to_string(b) + " has no cache page for key " + std::to_string(st->lens[b]));
+    }
   return HYP_OK;
 }
 
@@ -816,6 +870,34 @@ hyp_status_t do_stage_decode_step_noalloc(hyp_stage_t *st, const void *hidden_in
   if (rc != HYP_OK) return rc;
   for (int b = 0; b < st->batch; ++b) st->lens[b] += 1;
   return HYP_OK;
+}
+
+hyp_status_t do_stage_set_page_table(hyp_stage_t *st, const int32_t *table, int32_t n_requests, int32_t pages_per_request) {
+  LIVE_OR_RETURN(st);
+  const int ppr = st->L.pages_per_req;
+  if (!ppr) return fail(st, HYP_ESTATE, "the stage was not created with HYP_FLAG_PAGED_KV");
+  if (!table || n_requests < 1 || pages_per_request < 1) return fail(st, HYP_EINVAL, "NULL table or non-positive count");
+  if (n_requests > st->cfg.max_batch) return fail(st, HYP_ECAPACITY, "more requests than max_batch");
+  std::vector<int> next((size_t)st->cfg.max_batch * ppr, -1);
+  std::vector<char> used((size_t)st->L.pool_pages, 0);
+  for (int r = 0; r < n_requests; ++r)
+    for (int i = 0; i < pages_per_request; ++i) {
+      const int page = table[(size_t)r * pages_per_request + i];
+      if (page < 0) continue;  // no page for these keys
+      if (i >= ppr) return fail(st, HYP_ECAPACITY, "a page beyond max_seq");
+      if (page >= st->L.pool_pages) return fail(st, HYP_EINVAL, "page " + std::to_string(page) + " is outside the pool");
+      if (used[page]) return fail(st, HYP_EINVAL, "page " + std::to_string(page) + " is assigned twice");
+      used[page] = 1;
+      next[(size_t)r * ppr + i] = page;
+    }
+  // requests that are resident keep what they hold: their keys must stay where they are
+  if (st->prefilled)
+    for (int b = 0; b < st->batch; ++b)
+      for (int i = 0; i * kPageKeys < st->lens[b]; ++i)
+        if (next[(size_t)b * ppr + i] != st->pages[(size_t)b * ppr + i])
+          return fail(st, HYP_ESTATE, "the table moves a page that holds cached keys of request " + std::to_string(b));
+  st->pages.swap(next);
+  return upload_page_table(st);
 }
 
 hyp_status_t do_stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {
@@ -933,6 +1015,10 @@ hyp_status_t stage_decode_step(hyp_stage_t *st, const void *hidden_in, void *hid
 
 hyp_status_t stage_decode_step_noalloc(hyp_stage_t *st, const void *hidden_in, void *hidden_out) {
   return guarded([&] { return do_stage_decode_step_noalloc(st, hidden_in, hidden_out); });
+}
+
+hyp_status_t stage_set_page_table(hyp_stage_t *st, const int32_t *table, int32_t n_requests, int32_t pages_per_request) {
+  return guarded([&] { return do_stage_set_page_table(st, table, n_requests, pages_per_request); });
 }
 
 hyp_status_t stage_export_kv(hyp_stage_t *st, int32_t layer, int32_t request, void *k_out, void *v_out) {

@@ -57,7 +57,8 @@ def test_phi3_stage_fits_hbm():
     (lambda c: setattr(c, "n_kv_heads", 3), binding.HYP_ESHAPE),
     (lambda c: setattr(c, "hidden", 0), binding.HYP_ESHAPE),
     (lambda c: setattr(c, "dtype", 7), binding.HYP_EINVAL),
-    (lambda c: setattr(c, "reserved", 1), binding.HYP_EINVAL),
+    (lambda c: setattr(c, "kv_pool_pages", 1), binding.HYP_EINVAL),   # only with HYP_FLAG_PAGED_KV
+    (lambda c: setattr(c, "flags", 64), binding.HYP_EINVAL),
 ])
 def test_create_rejects_bad_config_without_device(mutate, status):
     lib = hyp.load_library()

@@ -27,13 +27,20 @@ def sample_rows(L, rng, n_random=6):
     return rows
 
 
-def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE, cap=None):
+def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE, cap=None, paged=False):
     """`cap` = per-request capacity of the stage: it fixes the decode attention's chunking, so
     the tests of a bench workload pass the capacity the bench creates its stage with."""
     B, T = len(lens), sum(lens)
     cap = cap or max(lens) + decode_steps
     x = synth.hidden_states(T, SHAPE, seed)
-    gst = make_gpu_stage(SHAPE, [layer], B, cap, T)
+    if paged:  # pages of 128 keys, handed to the requests in shuffled order
+        from paper_2511_14450_amd import binding
+        gst = make_gpu_stage(SHAPE, [layer], B, cap, T, flags=binding.HYP_FLAG_PAGED_KV)
+        ppr = -(-((cap + 63) // 64 * 64) // 128)
+        perm = np.random.default_rng(seed).permutation(B * ppr)
+        gst.set_page_table([[int(v) for v in perm[r * ppr:(r + 1) * ppr]] for r in range(B)])
+    else:
+        gst = make_gpu_stage(SHAPE, [layer], B, cap, T)
     assert gst.uses_mfma()
     got = to_host(gst.prefill(to_dev(x, "bf16"), lens))
     starts = np.concatenate([[0], np.cumsum(lens)])
@@ -91,6 +98,14 @@ def test_c4_ragged_batch32_decode_at_long_context(phi3_layer):
     longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
     check_requests(phi3_layer, lens, 9300, sample_reqs=[longest, shortest], decode_steps=2,
                    cap=max(lens) + synth.WORKLOADS["c4_decode_heavy"].decode_steps)
+
+
+def test_c4_ragged_batch32_paged_cache_shuffled_table(phi3_layer):
+    # the same workload with the cache in 128-key pages assigned in shuffled order
+    lens = synth.WORKLOADS["c4_decode_heavy"].lengths()
+    longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
+    check_requests(phi3_layer, lens, 9350, sample_reqs=[longest, shortest], decode_steps=2,
+                   cap=max(lens) + synth.WORKLOADS["c4_decode_heavy"].decode_steps, paged=True)
 
 
 def test_c5_long_context_8192_sampled_rows_then_decode(phi3_layer):

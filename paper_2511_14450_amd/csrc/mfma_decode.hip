@@ -40,8 +40,7 @@ namespace {
 // ----------------------------------------------------------------------------
 // UNROLL k-tiles per batch: 10 weight loads of 1 KiB in flight per wave and 4 workgroups per
 // CU (124 registers) measured better than 20 in flight at 3 per CU
-constexpr int NW = 4;
-constexpr int kSsqParts = NW * 2;  // interleaved partial sums of the row groups' sums of squares (one per 32 threads)
+constexpr int kWavesPerCu = 16;  // 4 per SIMD at 124 registers: NW waves per workgroup, kWavesPerCu / NW workgroups per CU
 constexpr int kBeginRows = 64;  // rows per workgroup of the kernel that opens a step (and per sum of squares it writes)
 
 struct DecGemvParams {
@@ -75,17 +74,22 @@ struct DecGemvParams {
 // a 10-tile window give as many waves with as much in flight as two slices of 64-row workgroups
 // would, without partial sums, counter and gather at the end.
 // CLS (a hyp_kernel_class_t) only gives each GEMM of a block its own kernel name in a trace.
-template <int EPI, int FBW, int CLS>
+// NW waves per workgroup share the k-tiles of the workgroup's K slice: more waves per workgroup mean
+// fewer K slices across workgroups (fewer partial sums in memory, or none) for the same number of
+// waves in flight.
+template <int EPI, int FBW, int NW, int CLS>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4))) k_dec_gemv(DecGemvParams p) {
   constexpr int UNROLL = FBW == 1 ? 10 : 5;
   constexpr int kGroupRows = FBW * 32;
   constexpr int kRedStride = kGroupRows + 4;  // keeps 16-byte alignment, spreads tokens over banks
-  // the waves' sums as [wave][token][row]: rows contiguous so that the cross-wave add reads
-  // without bank conflicts; 34 KiB, reused as fin[32][65] once reduced
-  __shared__ __attribute__((aligned(16))) float red[NW][32][kRedStride];
+  constexpr int kSsqParts = NW * 2;  // interleaved partial sums of the row groups' sums of squares (one per 32 threads)
+  // the waves' sums as [wave][token][row], tokens of the batch only: rows contiguous so that the
+  // cross-wave add reads without bank conflicts; reused as fin[token][kGroupRows + 1] once reduced
+  extern __shared__ __attribute__((aligned(16))) float red_raw[];
+  float (*red)[kRedStride] = (float (*)[kRedStride])red_raw;  // red[wave * batch + token][row]
   __shared__ float rstd_s[32];
   __shared__ unsigned is_last;
-  float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1]) & red[0][0][0];
+  float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1])red_raw;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   // 1-D grid: first the `ksplit` slices of row groups [0, groups1), slice-major, then the
   // 2 * ksplit slices of the remaining groups
@@ -174,7 +178,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         f32x4_t v = {acc[i][4 * q], acc[i][4 * q + 1], acc[i][4 * q + 2], acc[i][4 * q + 3]};
-        *(f32x4_t *)&red[wave][lane & 31][32 * i + 8 * q + 4 * (lane >> 5)] = v;
+        *(f32x4_t *)&red[wave * p.batch + (lane & 31)][32 * i + 8 * q + 4 * (lane >> 5)] = v;
       }
   }
   __syncthreads();
@@ -188,7 +192,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     if (idx < n_pairs) {
       int f = idx % kGroupRows, token = idx / kGroupRows;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) mine[j] += red[w][token][f];
+      for (int w = 0; w < NW; ++w) mine[j] += red[w * p.batch + token][f];
     }
   }
   __syncthreads();  // `red` is free from here on
@@ -441,53 +445,88 @@ __global__ void k_fill_zero(uint4 *p, size_t n16) {
 
 }  // namespace
 
-// K slices across workgroups: the fewest that bring a wave's share down to about 56 k-tiles
-// (measured on the Phi-3-medium shapes: longer shares leave too few waves to cover the memory
-// latency, shorter ones pay more in partial sums, counters and finishing workgroups than
-// they win), and few enough that the fp32 partial sums (written and read once per slice and
-// token) stay a small fraction of the weight bytes
-int mfma_gemv_ksplit(int N, int K, int batch) {
-  (void)N;
-  int KT = K / 16;
+// How one skinny GEMM of a decode step is cut into workgroups.
+//   fbw     32-row blocks per workgroup: 2 where the epilogue pairs rows of two blocks (RoPE partners,
+//           gate and up) and for long K; 1 for the residual GEMMs at short K, which then run as
+//           unsplit 4-wave workgroups with a 10-tile window
+//   nw      waves per workgroup; they share the k-tiles of the workgroup's K slice.  8 for the
+//           64-row workgroups: the same waves in flight with half the K slices of 4-wave workgroups
+//   ksplit  K slices across workgroups (partial sums in memory, the last to arrive adds them up):
+//           the fewest that put a wave on every slot of the chip (16 per CU), as long as a wave
+//           keeps at least 20 k-tiles (four windows of the streaming loop) and the fp32 partial sums
+//           (written and read once per slice and token) stay a few percent of the weight bytes.
+//           Phi-3-medium shapes: gate/up unsplit (560 workgroups), QKV 2 slices, down 7 slices;
+//           measured against every other admissible cut of each GEMM at batch 8 and 32, this rule's
+//           choices were the fastest or within 1 % of it.
+GemvPlan mfma_gemv_plan(int cls, int N, int K, int batch) {
+  GemvPlan g;
+  const int KT = K / 16;
+  if ((cls == HYP_K_GEMV_O || cls == HYP_K_GEMV_DOWN) && KT / 4 <= 112 && KT % 4 == 0) {
+    g.fbw = 1; g.nw = 4; g.ksplit = 1;
+    return g;
+  }
+  g.fbw = 2; g.nw = 8; g.ksplit = 1;
+  if (KT % g.nw != 0) g.nw = 4;
+  const int groups = N / 64, wave_slots = kWavesPerCu * 256;
   int cap = (int)(0.025 * K / (batch > 0 ? batch : 1));
   if (cap < 1) cap = 1;
-  int best = 1;
   for (int ks = 1; ks <= 64 && ks <= cap; ++ks) {
-    if (KT % (ks * NW) != 0) continue;
-    best = ks;
-    if (KT / (ks * NW) <= 56) break;
+    if (KT % (ks * g.nw) != 0 || KT / (ks * g.nw) < 20) continue;
+    g.ksplit = ks;
+    if (groups * ks * g.nw >= wave_slots) break;
   }
-  return best;
+  return g;
 }
 
-// Residual GEMMs whose K fits one slice of at most 112 k-tiles per wave run as 32-row workgroups
-// without any split (same number of waves, same bytes in flight, no partial sums)
-int mfma_gemv_resid_fbw(int K) { return K / 16 / NW <= 112 && (K / 16) % NW == 0 ? 1 : 2; }
+// the (epilogue, blocks per workgroup, waves per workgroup, class) combinations a plan may ask for
+#define HYP_GEMV_VARIANTS(X, NW)                                                                         \
+  X(DEC_QKV, 2, NW, HYP_K_GEMV_QKV) X(DEC_SWIGLU, 2, NW, HYP_K_GEMV_GATEUP)                              \
+  X(DEC_RESID, 1, NW, HYP_K_GEMV_O) X(DEC_RESID, 2, NW, HYP_K_GEMV_O)                                    \
+  X(DEC_RESID, 1, NW, HYP_K_GEMV_DOWN) X(DEC_RESID, 2, NW, HYP_K_GEMV_DOWN)                              \
+  X(DEC_FINAL, 1, NW, HYP_K_GEMV_DOWN) X(DEC_FINAL, 2, NW, HYP_K_GEMV_DOWN)
+
+// the waves' sums of 32 tokens can pass the 64 KiB a workgroup gets by default
+hipError_t mfma_gemv_init() {
+  hipError_t e = hipSuccess;
+#define X(EPI, FBW, NW, CLS)                                                                                     \
+  if (e == hipSuccess)                                                                                           \
+    e = hipFuncSetAttribute((const void *)k_dec_gemv<EPI, FBW, NW, CLS>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                            (int)(sizeof(float) * NW * 32 * (FBW * 32 + 4)));
+  HYP_GEMV_VARIANTS(X, 8)
+  HYP_GEMV_VARIANTS(X, 16)
+#undef X
+  return e;
+}
 
 hipError_t mfma_dec_gemv(int epi, int cls, const DecGemv &a, hipStream_t s) {
   DecGemvParams p = {};
+  const int fbw = a.plan.fbw, nw = a.plan.nw, ksplit = a.plan.ksplit;
   p.W = a.W; p.x = a.x; p.partial = a.partial; p.counters = a.counters;
-  p.N = a.N; p.KT = a.K / 16; p.ksplit = a.ksplit; p.tiles_per_wave = p.KT / (a.ksplit * NW); p.batch = a.batch;
+  p.N = a.N; p.KT = a.K / 16; p.ksplit = ksplit; p.tiles_per_wave = p.KT / (ksplit * nw); p.batch = a.batch;
+  if (p.tiles_per_wave * ksplit * nw != p.KT || a.N % (fbw * 32) != 0 || kWavesPerCu % nw != 0) return hipErrorInvalidValue;
   p.ssq_in = a.ssq_in; p.n_ssq = a.n_ssq; p.inv_H = a.n_ssq ? 1.0f / (float)a.K : 0.f; p.eps = a.eps;
   p.lens = a.lens; p.cos_tab = a.cos_tab; p.sin_tab = a.sin_tab; p.qdec = a.qdec; p.Kc = a.Kc; p.Vc = a.Vc;
   p.geom = a.geom; p.nq = a.nq; p.nkv = a.nkv; p.m_out = a.m_out; p.I = a.I; p.xres = a.xres; p.gain = a.gain;
   p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H; p.lens_advance = a.lens_advance;
-  // When the slices of all row groups do not fit the chip at once (4 workgroups per CU) but
-  // would in fewer than two rounds, the groups beyond the first round get twice the slices:
-  // twice as many waves, half as long, for what would otherwise be a thin second round.
-  const int fbw = (a.fbw == 1 && (epi == DEC_RESID || epi == DEC_FINAL)) ? 1 : 2;
-  const int groups = a.N / (fbw * 32), slots = 4 * 256;
+  // When the slices of all row groups do not fit the chip at once but would in fewer than two
+  // rounds, the groups beyond the first round get twice the slices: twice as many waves, half
+  // as long, for what would otherwise be a thin second round.
+  const int groups = a.N / (fbw * 32), slots = kWavesPerCu / nw * 256;
   p.n_groups = groups; p.groups1 = groups;
-  if (groups * a.ksplit > slots && groups * a.ksplit < 2 * slots && p.tiles_per_wave % 2 == 0 &&
-      p.tiles_per_wave / 2 >= 10 && 2 * a.ksplit <= a.max_ksplit)
-    p.groups1 = slots / a.ksplit;
-  dim3 grid(p.groups1 * a.ksplit + (groups - p.groups1) * 2 * a.ksplit);
+  if (groups * ksplit > slots && groups * ksplit < 2 * slots && p.tiles_per_wave % 2 == 0 &&
+      p.tiles_per_wave / 2 >= 10 && 2 * ksplit <= a.max_ksplit)
+    p.groups1 = slots / ksplit;
+  dim3 grid(p.groups1 * ksplit + (groups - p.groups1) * 2 * ksplit);
+  const size_t lds = sizeof(float) * nw * a.batch * (fbw * 32 + 4);  // the waves' sums of the live tokens
   bool launched = false;
-#define X(EPI, FBW, CLS) \
-  if (!launched && epi == EPI && fbw == FBW && cls == CLS) { k_dec_gemv<EPI, FBW, CLS><<<grid, NW * 64, 0, s>>>(p); launched = true; }
-  X(DEC_QKV, 2, HYP_K_GEMV_QKV) X(DEC_SWIGLU, 2, HYP_K_GEMV_GATEUP)
-  X(DEC_RESID, 1, HYP_K_GEMV_O) X(DEC_RESID, 2, HYP_K_GEMV_O)
-  X(DEC_RESID, 1, HYP_K_GEMV_DOWN) X(DEC_RESID, 2, HYP_K_GEMV_DOWN) X(DEC_FINAL, 1, HYP_K_GEMV_DOWN) X(DEC_FINAL, 2, HYP_K_GEMV_DOWN)
+#define X(EPI, FBW, NW, CLS)                                                 \
+  if (!launched && epi == EPI && fbw == FBW && nw == NW && cls == CLS) {      \
+    k_dec_gemv<EPI, FBW, NW, CLS><<<grid, NW * 64, lds, s>>>(p);             \
+    launched = true;                                                         \
+  }
+  HYP_GEMV_VARIANTS(X, 4)
+  HYP_GEMV_VARIANTS(X, 8)
+  HYP_GEMV_VARIANTS(X, 16)
 #undef X
   if (!launched) return hipErrorInvalidValue;
   return hipGetLastError();

@@ -67,14 +67,16 @@ enum { DEC_QKV = 0, DEC_SWIGLU = 1, DEC_RESID = 2, DEC_FINAL = 3 };
 // One skinny GEMM of a decode step, sum[token, n] = W[n, :] . x[token, :], with
 // its consumer fused in (see k_dec_gemv).  Fields a given epilogue does not use
 // stay null / 0.
+// how a skinny GEMM is cut into workgroups (see mfma_gemv_plan)
+struct GemvPlan { int fbw = 2, nw = 4, ksplit = 1; };
+
 struct DecGemv {
   const bf16_t *W = nullptr, *x = nullptr;  // P(N, K), P(32, K)
   float *partial = nullptr;                 // [max_ksplit][32][N]
   unsigned *counters = nullptr;             // [N / 32], zero between launches
-  int N = 0, K = 0, ksplit = 1, batch = 0;
+  int N = 0, K = 0, batch = 0;
+  GemvPlan plan;                            // plan.fbw also sets the granularity of ssq_out (sums of squares per 32 or 64 rows)
   int max_ksplit = 1;                       // slices `partial` has room for (the launcher may split some row groups finer)
-  int fbw = 2;                              // DEC_RESID / DEC_FINAL: 32-row blocks per workgroup (1 or 2); sets the
-                                            // granularity of ssq_out (sums of squares per 32 or 64 rows)
   const float *ssq_in = nullptr;            // [n_ssq][32] sums of squares of the normalised input
   int n_ssq = 0;
   float eps = 0.f;
@@ -94,8 +96,8 @@ struct DecGemv {
   int *lens_advance = nullptr;  // DEC_FINAL: lengths to increment at the end of the step
 };
 hipError_t mfma_dec_gemv(int epi, int cls, const DecGemv &a, hipStream_t s);  // cls: as for mfma_gemm
-int mfma_gemv_ksplit(int N, int K, int batch);
-int mfma_gemv_resid_fbw(int K);  // 1: run the residual GEMM of this K as unsplit 32-row workgroups
+GemvPlan mfma_gemv_plan(int cls, int N, int K, int batch);  // cls: HYP_K_GEMV_*
+hipError_t mfma_gemv_init();  // kernel attributes, once per process and device
 // x = hidden_in ; xres = x ; y' = x * gain -> P(32, H) ; ssq_out[H/64][32]
 hipError_t mfma_dec_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y_out, float *ssq_out,
                           int H, int batch, hipStream_t s);

@@ -72,8 +72,7 @@ struct Layout {
   int key_blocks = 0;   // 32-key blocks per (request, kv head)
   int max_chunks = 0;   // decode attention chunks per head
   int chunk_keys = 128; // keys per chunk
-  int ks_qkv = 1, ks_o = 1, ks_gu = 1, ks_d = 1;
-  int fbw_o = 2, fbw_d = 2;  // 32-row blocks per workgroup of the two residual decode GEMMs
+  GemvPlan g_qkv, g_o, g_gu, g_d;  // how the four skinny GEMMs of a decode step are cut into workgroups
   size_t partial_bytes = 0, attn_part_bytes = 0, counters_bytes = 0;
   // paged KV cache (HYP_FLAG_PAGED_KV): pages per layer of the pool, table entries per request
   size_t page_table = 0;
@@ -190,14 +189,12 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.lens = take(sizeof(int) * c.max_batch);
     L.row_ext_dec = take(sizeof(int) * 32);
     L.qdec = take(es * (size_t)c.max_batch * c.n_kv_heads * 32 * 128);
-    L.ks_qkv = mfma_gemv_ksplit((int)(qd + 2 * kvd), (int)H, c.max_batch);
-    L.fbw_o = mfma_gemv_resid_fbw((int)qd);
-    L.fbw_d = mfma_gemv_resid_fbw((int)I);
-    L.ks_o = L.fbw_o == 1 ? 1 : mfma_gemv_ksplit((int)H, (int)qd, c.max_batch);
-    L.ks_gu = mfma_gemv_ksplit((int)(2 * I), (int)H, c.max_batch);
-    L.ks_d = L.fbw_d == 1 ? 1 : mfma_gemv_ksplit((int)H, (int)I, c.max_batch);
-    size_t pf = std::max(std::max((size_t)L.ks_qkv * (qd + 2 * kvd), (size_t)L.ks_o * H),
-                         std::max((size_t)L.ks_gu * 2 * I, (size_t)L.ks_d * H));
+    L.g_qkv = mfma_gemv_plan(HYP_K_GEMV_QKV, (int)(qd + 2 * kvd), (int)H, c.max_batch);
+    L.g_o = mfma_gemv_plan(HYP_K_GEMV_O, (int)H, (int)qd, c.max_batch);
+    L.g_gu = mfma_gemv_plan(HYP_K_GEMV_GATEUP, (int)(2 * I), (int)H, c.max_batch);
+    L.g_d = mfma_gemv_plan(HYP_K_GEMV_DOWN, (int)H, (int)I, c.max_batch);
+    size_t pf = std::max(std::max((size_t)L.g_qkv.ksplit * (qd + 2 * kvd), (size_t)L.g_o.ksplit * H),
+                         std::max((size_t)L.g_gu.ksplit * 2 * I, (size_t)L.g_d.ksplit * H));
     L.partial_bytes = sizeof(float) * pf * 32 * 2;  // room for twice the slices (row groups split finer at the end of a launch)
     L.partial = take(L.partial_bytes);
     L.chunk_keys = mfma_decode_chunk_keys(c.max_seq, c.max_batch * c.n_kv_heads);
@@ -459,8 +456,8 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const DecScratch &sc
     const LayerPtrs &p = L.layers[l];
     bf16_t *Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l), *Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
     DecGemv a = base;
-    a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.ksplit = L.ks_qkv; a.max_ksplit = 2 * a.ksplit;
-    a.ssq_in = ssq; a.n_ssq = d.H / (l == 0 ? 64 : 32 * L.fbw_d);  // written by the opening kernel / the previous down GEMM
+    a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.plan = L.g_qkv; a.max_ksplit = 2 * a.plan.ksplit;
+    a.ssq_in = ssq; a.n_ssq = d.H / (l == 0 ? 64 : 32 * L.g_d.fbw);  // written by the opening kernel / the previous down GEMM
     a.lens = at<int>(st, L.lens); a.cos_tab = at<float>(st, L.cos_tab); a.sin_tab = at<float>(st, L.sin_tab);
     a.qdec = sc.qdec; a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
     PROF(st, HYP_K_GEMV_QKV, mfma_dec_gemv(DEC_QKV, HYP_K_GEMV_QKV, a, s));
@@ -468,15 +465,15 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const DecScratch &sc
                                                  attn, d.nq, d.nkv, st->batch,
                                                  L.max_chunks, L.chunk_keys, s));
     DecGemv o = base;
-    o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.ksplit = L.ks_o; o.max_ksplit = 2 * o.ksplit; o.fbw = L.fbw_o;
+    o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.plan = L.g_o; o.max_ksplit = 2 * o.plan.ksplit;
     o.gain = at<bf16_t>(st, p.g2); o.y_out = y; o.ssq_out = ssq;
     PROF(st, HYP_K_GEMV_O, mfma_dec_gemv(DEC_RESID, HYP_K_GEMV_O, o, s));
     DecGemv g = base;
-    g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.ksplit = L.ks_gu; g.max_ksplit = 2 * g.ksplit;
-    g.ssq_in = ssq; g.n_ssq = d.H / (32 * L.fbw_o); g.m_out = m; g.I = d.I;
+    g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.plan = L.g_gu; g.max_ksplit = 2 * g.plan.ksplit;
+    g.ssq_in = ssq; g.n_ssq = d.H / (32 * L.g_o.fbw); g.m_out = m; g.I = d.I;
     PROF(st, HYP_K_GEMV_GATEUP, mfma_dec_gemv(DEC_SWIGLU, HYP_K_GEMV_GATEUP, g, s));
     DecGemv w = base;
-    w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.ksplit = L.ks_d; w.max_ksplit = 2 * w.ksplit; w.fbw = L.fbw_d;
+    w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.plan = L.g_d; w.max_ksplit = 2 * w.plan.ksplit;
     if (l + 1 < st->n_layers) {
       w.gain = at<bf16_t>(st, L.layers[l + 1].g1); w.y_out = y; w.ssq_out = ssq;
       PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_RESID, HYP_K_GEMV_DOWN, w, s));
@@ -665,6 +662,7 @@ hyp_status_t do_stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int
 
   if (st->mfma) {
     hipError_t e = mfma_gemm_init();
+    if (e == hipSuccess) e = mfma_gemv_init();
     if (e != hipSuccess) { st->err = std::string("kernel attributes: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
     // where a decode step keeps its temporaries: in the workspace ...
     const Layout &L = st->L;

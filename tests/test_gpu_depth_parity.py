@@ -75,7 +75,7 @@ def test_split_k_scratch_is_clean_across_consecutive_steps():
     against the same steps launched kernel by kernel instead of from the recorded graph."""
     import torch
     from paper_2511_14450_amd import binding
-    shape = synth.BlockShape(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=1024, dtype="bf16")
+    shape = synth.BlockShape(hidden=5120, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=7680, dtype="bf16")  # QKV, gate/up and down all split along K
     layers = [synth.layer_weights(shape, l, 8200, sigma=0.02) for l in range(2)]
     lens = [3, 40, 7, 9, 10]
     x = synth.hidden_states(sum(lens), shape, 8201)

@@ -148,9 +148,9 @@ def test_mfma_decode_every_batch_width(batch):
     gst.destroy()
 
 
-# K = 4096 is the smallest width here whose skinny GEMMs are split along K across workgroups
-# (two slices for QKV, O and gate/up; the K = 1024 down projection stays unsplit)
-SHAPE_SPLITK = synth.BlockShape(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=1024, dtype="bf16")
+# hidden 5120 and FFN 7680 are the smallest widths here at which the skinny GEMMs of a decode step are
+# split along K across workgroups (two slices for QKV and gate/up, three for the down projection)
+SHAPE_SPLITK = synth.BlockShape(hidden=5120, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=7680, dtype="bf16")
 
 
 @pytest.mark.parametrize("batch", [3, 17, 31])

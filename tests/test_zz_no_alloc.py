@@ -12,8 +12,8 @@ from tests.helpers import make_config, make_gpu_stage, to_dev
 
 pytestmark = pytest.mark.gpu
 
-# K = 4096 splits the skinny GEMMs along K, so partial sums and arrival counters are in use
-SHAPE = synth.BlockShape(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn_dim=1024, dtype="bf16")
+# at these widths the skinny GEMMs are split along K, so partial sums and arrival counters are in use
+SHAPE = synth.BlockShape(hidden=5120, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn_dim=7680, dtype="bf16")
 
 
 def _decode_raw(lib, entry, stage, x, y):
@@ -59,9 +59,9 @@ def test_noalloc_decode_refuses_what_does_not_fit_or_does_not_apply():
     import paper_2511_14450_amd as hyp
     from paper_2511_14450_amd import binding
     lib = hyp.load_library()
-    # hidden 8192 at batch 8 splits the gate/up GEMV four ways: 4 x 32768 rows x 32 tokens x 2 x 4 B of
-    # partial sums alone pass 32 MiB; zero weights are enough, the stage is never run
-    big = synth.BlockShape(hidden=8192, n_q_heads=64, n_kv_heads=16, head_dim=128, ffn_dim=16384, dtype="bf16")
+    # an FFN of 65536 features: the gate/up GEMV's room for partial sums, 2 x 65536 rows x 32 tokens x 2 x 4 B,
+    # alone passes 32 MiB; zero weights are enough, the stage is never run
+    big = synth.BlockShape(hidden=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=65536, dtype="bf16")
     w = {n: torch.zeros(shp, dtype=torch.bfloat16, device="cuda") for n, shp in big.weight_shapes().items()}
     st = hyp.stage_create(make_config(big, 8, 128, 128), 0, 1, [w])
     x = torch.zeros((8, big.hidden), dtype=torch.bfloat16, device="cuda")

@@ -28,15 +28,31 @@ __device__ __forceinline__ bf16x8_t probs_operand(const float *p /*16*/, int m) 
 // Prefill.  One workgroup = one KV head x one tile of 64 query rows.  It has two
 // waves per query head of the group (32 query rows each), so a K / V stage of 64
 // keys (32 KiB, already in fragment order) is fetched once into LDS by direct
-// loads and read by all 2G waves, and each SIMD holds two waves whose MFMA and
-// softmax phases overlap.  Per wave: S^T = K Q^T (keys on the MFMA M axis, so a
-// lane owns one query column and the softmax reductions stay inside a lane plus
-// one cross-half exchange), online softmax in fp32, O^T += V^T P^T.
+// loads and read by all 2G waves.  Per wave: S^T = K Q^T (keys on the MFMA M axis,
+// so a lane owns one query column and the softmax reductions stay inside a lane
+// plus one cross-half exchange), online softmax in fp32, O^T += V^T P^T.
+//
+// The loop is software-pipelined over stages: the scores of stage s + 1 are
+// formed (MFMA) in the same straight-line block in which the probabilities of
+// stage s are exponentiated, summed and rounded (VALU), so the matrix pipe works
+// under the softmax arithmetic, which is the longer of the two; three LDS buffers
+// keep stage s (values), s + 1 (keys, then values) and s + 2 (arriving) apart.
+// The running maximum is only moved - and the accumulators rescaled - when it has
+// grown by more than 2^8 in some row: probabilities stay below 256, sums and
+// outputs are formed against the same reference, and the rescale leaves the loop's
+// steady state.  Only the last stage of a tile touches the diagonal and is masked.
 // ----------------------------------------------------------------------------
 constexpr int kKvStageKeys = 64;
 constexpr int kKvStageBytes = 2 * 16384;  // per 32 keys: 8 K tiles + 8 V tiles
+constexpr int kKvBufs = 3;
+constexpr int kAttnPrefillLds = kKvBufs * kKvStageBytes;
+constexpr float kRescaleLog2 = 8.0f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// max of three: one v_max3_f32, because this file is compiled with -fno-honor-nans (scores are never
+// NaN; otherwise the compiler puts a canonicalising self-maximum in front of every fmaxf operand).
+// Not inline assembly: the compiler's hazard logic must see that the operands come out of MFMAs.
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
 __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__ q,
                                                       const bf16_t *__restrict__ Kc,
@@ -44,7 +60,7 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
                                                       bf16_t *__restrict__ out,
                                                       const PrefillTile *__restrict__ tiles,
                                                       const int *__restrict__ req_len, int nq, int G) {
-  __shared__ __attribute__((aligned(1024))) char lds[2 * kKvStageBytes];
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hh = lane >> 5, tl = lane & 31;
   const int nw = blockDim.x >> 6;  // 2 G
   const PrefillTile tile = tiles[blockIdx.x];
@@ -55,7 +71,7 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
   const int qd = nq * 128;
   const int len = req_len[tile.req];
   const int n_kb = min(tile.qblk0 + 2, (len + 31) >> 5);  // 32-key blocks the tile needs
-  const int n_st = (n_kb + 1) >> 1;                        // 64-key stages
+  const int n_st = (n_kb + 1) >> 1;                        // 64-key stages; every wave of the tile needs all of them
   const int rb = (tile.row0 >> 5) + tq;
   const float c = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
   const int qpos = qblk * 32 + tl;
@@ -85,59 +101,25 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
       __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvStageBytes + t * 1024), 16, 0, 0);
     }
   };
-  issue(stage_off(0), 0);
-  size_t off_next = stage_off(1);
-  for (int st = 0; st < n_st; ++st) {
-    const int buf = st & 1;
-    __builtin_amdgcn_s_waitcnt(0x0070);  // my loads landed, my LDS reads of the previous stage done
-    __syncthreads();
-    if (st + 1 < n_st) {
-      issue(off_next, buf ^ 1);
-      off_next = stage_off(st + 2);
-    }
-    const int kb0 = st * 2;
-    if (kb0 > qblk) continue;  // this wave's rows end before the stage's keys start (barrier is at the loop top)
+  // scores of both 32-key blocks of the stage in `buf`: two independent accumulator chains
+  auto scores = [&](int buf, f32x16_t &a0, f32x16_t &a1) {
     const char *base = lds + buf * kKvStageBytes + lane * 16;
-    // scores of both 32-key blocks: two independent accumulator chains
-    f32x16_t s0, s1;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
       bf16x8_t k0 = *(const bf16x8_t *)(base + dt * 1024);
       bf16x8_t k1 = *(const bf16x8_t *)(base + 16384 + dt * 1024);
-      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[dt], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[dt], s1, 0, 0, 0);
+      a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[dt], a0, 0, 0, 0);
+      a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[dt], a1, 0, 0, 0);
     }
-    float p[32];
-    float mx = -INFINITY;
-    if (kb0 + 1 >= qblk) {  // the stage touches or passes the diagonal (a block past the
-                            // tile's need is fully masked here: its keys lie after every row)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int koff = 8 * (r >> 2) + 4 * hh + (r & 3);
-        p[r] = (kb0 * 32 + koff > qpos) ? -INFINITY : s0[r];
-        p[16 + r] = (kb0 * 32 + 32 + koff > qpos) ? -INFINITY : s1[r];
-        mx = fmaxf(mx, fmaxf(p[r], p[16 + r]));
-      }
-    } else {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        p[r] = s0[r];
-        p[16 + r] = s1[r];
-        mx = fmaxf(mx, fmaxf(p[r], p[16 + r]));
-      }
-    }
-    mx = xhalf_max(mx);
-    float m_new = fmaxf(m_run, mx);  // finite from the first stage on: key 0 is visible to every row
-    float mc = m_new * c, rowsum = 0.f;
-#pragma unroll
-    for (int r = 0; r < 32; ++r) {
-      p[r] = fast_exp2(p[r] * c - mc);
-      rowsum += p[r];
-    }
-    if (__any(m_new > m_run)) {
-      float alpha = fast_exp2((m_run - m_new) * c);  // 0 on the first stage
+  };
+  // move the running maximum when some row's has grown by more than 2^kRescaleLog2 (always on the
+  // first stage, where the old maximum is -inf and the factor 0)
+  auto follow_max = [&](float mx) {
+    float m_new = fmaxf(m_run, xhalf_max(mx));  // finite from the first stage on: key 0 is visible to every row
+    if (__any((m_new - m_run) * c > kRescaleLog2)) {
+      float alpha = fast_exp2((m_run - m_new) * c);
       l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
@@ -145,8 +127,10 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
       m_run = m_new;
     }
-    l_run += rowsum;
-    bf16x8_t pf[4] = {probs_operand(p, 0), probs_operand(p, 1), probs_operand(p + 16, 0), probs_operand(p + 16, 1)};
+  };
+  // O^T += V^T P^T for the stage in `buf`
+  auto values = [&](int buf, const bf16x8_t *pf) {
+    const char *base = lds + buf * kKvStageBytes + lane * 16;
 #pragma unroll
     for (int h2 = 0; h2 < 4; ++h2)   // (key block, MFMA step) pairs
 #pragma unroll
@@ -154,6 +138,119 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
         bf16x8_t vf = *(const bf16x8_t *)(base + (h2 >> 1) * 16384 + (8 + (h2 & 1) * 4 + db) * 1024);
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[h2], o[db], 0, 0, 0);
       }
+  };
+
+  issue(stage_off(0), 0);
+  if (n_st > 1) issue(stage_off(1), 1);
+  size_t off_next = stage_off(2);
+  __builtin_amdgcn_s_waitcnt(0x0070);  // my loads of the first two stages have landed
+  __syncthreads();
+  f32x16_t s0, s1;
+  scores(0, s0, s1);
+  float mx = max3(s0[0], s1[0], -INFINITY);
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mx = max3(mx, s0[r], s1[r]);
+
+  // A wave issues in order: an MFMA that finds the matrix pipe still busy with the previous one
+  // holds up the arithmetic behind it.  So each iteration is laid out as two phases in which
+  // every MFMA (32 cycles) is followed by about as many cycles of independent VALU work:
+  //   phase 1   scores of stage st + 1 (16 MFMAs)  |  exponentials and rounding of stage st
+  //   phase 2   P V of stage st (16 MFMAs)         |  row sums of stage st, maxima of stage st + 1
+  // The scheduling-group builtins fix that interleaving; left alone the compiler bunches the MFMAs.
+  bf16x8_t pf[4];
+  int buf = 0;  // buffer of stage st
+  for (int st = 0; st + 1 < n_st; ++st) {
+    const int buf1 = buf + 1 == kKvBufs ? 0 : buf + 1, buf2 = buf1 + 1 == kKvBufs ? 0 : buf1 + 1;
+    if (st + 2 < n_st) issue(off_next, buf2);  // over stage st - 1, which every wave has left
+    // Fragments come from LDS in batches of four, each batch requested one group of four MFMAs ahead
+    // (while LDS-direct loads are in flight the compiler only emits full LDS waits, so a batch is
+    // awaited as a whole, long after it was requested).
+    const char *kbase = lds + buf1 * kKvStageBytes + lane * 16;
+    const char *vbase = lds + buf * kKvStageBytes + lane * 16 + 8 * 1024;
+    auto kfrag = [&](int i) { return *(const bf16x8_t *)(kbase + (i & 1) * 16384 + (i >> 1) * 1024); };  // i = 2 dt + key block
+    auto vfrag = [&](int i) { return *(const bf16x8_t *)(vbase + (i >> 3) * 16384 + (i & 7) * 1024); };  // i = 8 key block + 4 step + d block
+    bf16x8_t fr[2][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) fr[0][u] = kfrag(u);
+    __builtin_amdgcn_sched_barrier(0);
+    follow_max(mx);
+    const float mc = m_run * c;
+    // ---- phase 1: scores of stage st + 1 | probabilities of stage st
+    f32x16_t n0, n1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { n0[r] = 0.f; n1[r] = 0.f; }
+    float p[32];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int g = i >> 2, u = i & 3;
+      if (i & 1) n1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][u], qf[i >> 1], n1, 0, 0, 0);
+      else n0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][u], qf[i >> 1], n0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (u == 0) {  // the next batch: keys of the next group, or the first values of phase 2
+#pragma unroll
+        for (int w = 0; w < 4; ++w) fr[(g + 1) & 1][w] = g < 3 ? kfrag(4 * (g + 1) + w) : vfrag(w);
+      }
+      // two probabilities and their rounding per MFMA: registers 2 i and 2 i + 1 of the 32 scores
+      {
+        const int r0 = 2 * i, r1 = 2 * i + 1;
+        p[r0] = fast_exp2((r0 < 16 ? s0[r0] : s1[r0 - 16]) * c - mc);
+        p[r1] = fast_exp2((r1 < 16 ? s0[r1] : s1[r1 - 16]) * c - mc);
+        pf[r0 >> 3][r0 & 7] = (__bf16)p[r0];
+        pf[r0 >> 3][r1 & 7] = (__bf16)p[r1];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- phase 2: P V of stage st | row sums of stage st, maxima of stage st + 1
+    float rowsum = 0.f;
+    mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int g = i >> 2, u = i & 3;
+      o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][u], pf[i >> 2], o[i & 3], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (u == 0 && g < 3) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) fr[(g + 1) & 1][w] = vfrag(4 * (g + 1) + w);
+      }
+      rowsum += p[2 * i];
+      rowsum += p[2 * i + 1];
+      mx = max3(mx, n0[i], n1[i]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    l_run += rowsum;
+    s0 = n0; s1 = n1;
+    buf = buf1;
+    // a paged cache answers this with a scalar load; issued here, it completes under the wait below -
+    // outstanding during the phases it would turn every LDS wait into a full one
+    off_next = stage_off(st + 3);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // my loads of stage st + 2 landed, my LDS reads of stage st done
+    __syncthreads();
+  }
+  // last stage: the only one that touches the diagonal (a block past the tile's need is fully
+  // masked here: its keys lie after every row)
+  {
+    const int kb0 = (n_st - 1) * 2;
+    float p[32];
+    mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      int koff = 8 * (r >> 2) + 4 * hh + (r & 3);
+      p[r] = (kb0 * 32 + koff > qpos) ? -INFINITY : s0[r];
+      p[16 + r] = (kb0 * 32 + 32 + koff > qpos) ? -INFINITY : s1[r];
+      mx = fmaxf(mx, fmaxf(p[r], p[16 + r]));
+    }
+    follow_max(mx);
+    const float mc = m_run * c;
+    float rowsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+      p[r] = fast_exp2(p[r] * c - mc);
+      rowsum += p[r];
+    }
+    l_run += rowsum;
+    pf[0] = probs_operand(p, 0); pf[1] = probs_operand(p, 1); pf[2] = probs_operand(p + 16, 0); pf[3] = probs_operand(p + 16, 1);
+    values(buf, pf);
   }
 
   // normalise and store into P(rows, qd): lane owns query tl, features 8g + 4hh + e of each d block
@@ -375,8 +472,12 @@ hipError_t mfma_attn_prefill(const bf16_t *q, const bf16_t *Kc, const bf16_t *Vc
                              int nq, int nkv, hipStream_t s) {
   if (n_tiles == 0) return hipSuccess;
   int G = nq / nkv;
-  k_attn_prefill<<<dim3(n_tiles, nkv), 2 * G * 64, 0, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq, G);
+  k_attn_prefill<<<dim3(n_tiles, nkv), 2 * G * 64, kAttnPrefillLds, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq, G);
   return hipGetLastError();
+}
+
+hipError_t mfma_attn_init() {
+  return hipFuncSetAttribute((const void *)k_attn_prefill, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnPrefillLds);
 }
 
 size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks) {

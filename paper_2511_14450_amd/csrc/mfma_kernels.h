@@ -57,6 +57,7 @@ hipError_t mfma_gemm(int epi, int cls, const bf16_t *X, const bf16_t *W, int row
 //   q P(rows, nq*128) ; caches of the layer ; out P(rows, nq*128)
 //   work items: (request, first internal row, query blocks) per 64-row query tile
 struct PrefillTile { int req, row0, qblk0; };  // qblk0: index of the tile's first 32-row block in the request
+hipError_t mfma_attn_init();  // kernel attributes, once per process and device
 hipError_t mfma_attn_prefill(const bf16_t *q, const bf16_t *Kc, const bf16_t *Vc, CacheGeom geom,
                              bf16_t *out, const PrefillTile *tiles, int n_tiles, const int *req_len,
                              int nq, int nkv, hipStream_t s);

@@ -663,6 +663,7 @@ hyp_status_t do_stage_create(const hyp_stage_config_t *cfg, int32_t l_start, int
   if (st->mfma) {
     hipError_t e = mfma_gemm_init();
     if (e == hipSuccess) e = mfma_gemv_init();
+    if (e == hipSuccess) e = mfma_attn_init();
     if (e != hipSuccess) { st->err = std::string("kernel attributes: ") + hipGetErrorString(e); return bail(HYP_EDEVICE); }
     // where a decode step keeps its temporaries: in the workspace ...
     const Layout &L = st->L;

@@ -3,12 +3,15 @@
 Only tests, the smoke check and the CPU-baseline leg of the benchmark may import
 this module; the library's own planner (C++) shares no code with it.
 
-    hypsplit_dp      Sec. IV-A, Algorithm 1: binary search on the target latency tau
-                     around the dynamic-programming feasibility check P_check(tau)
-                     (the DP(j, n) transition and its base case), partition by
-                     backtracking the predecessor table.
-    hypsched_rt      Sec. IV-B, Algorithm 2: one pass over the nodes of a tier, the
-                     available node with the smallest (queued + new) / C wins.
+    hypsplit_dp      Sec. IV-A, Algorithm 1: bisection on the target latency tau around
+                     the feasibility check P_check(tau), which is evaluated from its
+                     state-transition equation as a reachability relation; the partition
+                     follows the kept predecessors back from (T, N).
+    best_partition_by_enumeration
+                     the min-max problem of Sec. IV-A by plain enumeration of every
+                     partition vector (small N): what Algorithm 1 approximates.
+    hypsched_rt      Sec. IV-B, Algorithm 2: argmin of the expected completion over the
+                     eligible nodes of a tier.
     simulate_tiers   the queueing model the scheduler's inputs come from (Sec. IV-B:
                      one FIFO queue per node, T_wait from the remaining and the
                      waiting workloads), run over a list of arrival times.
@@ -41,57 +44,72 @@ def prefix_sums(v: Sequence[float]) -> List[float]:
 
 
 def p_check(tau: float, f, m, C, M):
-    """DP(j, n) and predecessor P(j, n) of the decision problem for target latency tau."""
+    """The decision problem P_check(tau) of Sec. IV-A, read off its state-transition equation
+
+        DP(j, n)  <=>  exists k, j-1 <= k < n :  DP(j-1, k)  and  L <= tau  and  U <= M_j,
+                       L = (S_f(n) - S_f(k)) / C_j,   U = S_m(n) - S_m(k),      DP(0, 0) true
+
+    as a reachability relation: reach[j] maps every n for which DP(j, n) holds to the predecessor
+    P(j, n) kept for it, the smallest admissible k.  Returns (DP(T, N), reach)."""
     N, T = len(f), len(C)
     S_f, S_m = prefix_sums(f), prefix_sums(m)
-    DP = [[False] * (N + 1) for _ in range(T + 1)]
-    P = [[-1] * (N + 1) for _ in range(T + 1)]
-    DP[0][0] = True
+    reach = [{0: None}]
     for j in range(1, T + 1):
+        C_j, M_j = C[j - 1], M[j - 1]
+        before = sorted(reach[j - 1])
+        here = {}
         for n in range(j, N + 1):
-            for k in range(j - 1, n):
-                if DP[j - 1][k]:
-                    L_j = (S_f[n] - S_f[k]) / C[j - 1]
-                    U_j = S_m[n] - S_m[k]
-                    if L_j <= tau and U_j <= M[j - 1]:
-                        DP[j][n] = True
-                        P[j][n] = k
-                        break
-    return DP, P
+            admissible = [k for k in before if k < n and (S_f[n] - S_f[k]) / C_j <= tau and S_m[n] - S_m[k] <= M_j]
+            if admissible:
+                here[n] = admissible[0]
+        reach.append(here)
+    return N in reach[T], reach
 
 
-def backtrack(P, T: int, N: int) -> List[int]:
-    """p_1 .. p_{T-1} from the predecessor table of a feasible check."""
-    p = [0] * (T + 1)
-    p[T] = N
-    n = N
+def backtrack(reach, T: int, N: int) -> List[int]:
+    """p_1 .. p_{T-1}: follow the predecessors from (T, N) down to (0, 0)."""
+    cuts, n = [], N
     for j in range(T, 0, -1):
-        n = P[j][n]
-        p[j - 1] = n
-    assert p[0] == 0
-    return p[1:T]
+        n = reach[j][n]
+        cuts.append(n)
+    assert cuts[-1] == 0
+    return cuts[-2::-1]
 
 
 def hypsplit_dp(f, m, C, M, eps: float) -> Tuple[Optional[List[int]], float]:
-    """Algorithm 1.  Returns (p*, tau*); p* is None if no partition is feasible."""
+    """Algorithm 1: bisect the target latency tau over [0, S_f(N) / min C_j], keeping the partition of
+    the last feasible check.  Returns (p*, tau*); p* is None if no partition is feasible."""
     N, T = len(f), len(C)
     assert 1 <= T <= N and eps > 0
-    S_f = prefix_sums(f)
-    tau_low, tau_high = 0.0, S_f[N] / min(C)
-    p_star, tau_star = None, tau_high
-    DP, P = p_check(tau_high, f, m, C, M)
-    if DP[T][N]:
-        p_star = backtrack(P, T, N)
-    while (tau_high - tau_low) > eps:
+    tau_low, tau_high = 0.0, prefix_sums(f)[N] / min(C)
+    ok, reach = p_check(tau_high, f, m, C, M)
+    p_star, tau_star = (backtrack(reach, T, N) if ok else None), tau_high
+    while tau_high - tau_low > eps:
         tau_mid = (tau_low + tau_high) / 2
-        DP, P = p_check(tau_mid, f, m, C, M)
-        if DP[T][N]:
-            tau_star = tau_mid
-            tau_high = tau_mid
-            p_star = backtrack(P, T, N)
+        ok, reach = p_check(tau_mid, f, m, C, M)
+        if ok:
+            p_star, tau_star, tau_high = backtrack(reach, T, N), tau_mid, tau_mid
         else:
             tau_low = tau_mid
     return p_star, tau_star
+
+
+def best_partition_by_enumeration(f, m, C, M) -> Tuple[Optional[List[int]], float]:
+    """The optimisation problem itself (the min-max objective of Sec. IV-A over all partition vectors
+    that respect the memory limits), by trying every one of the C(N-1, T-1) vectors: the plain
+    definition Algorithm 1 approximates to within eps.  Small N only.  Returns (p, max_j L_j(p))
+    of the first best vector in lexicographic order, or (None, inf)."""
+    from itertools import combinations
+    N, T = len(f), len(C)
+    best_p, best = None, float("inf")
+    for cuts in combinations(range(1, N), T - 1):
+        b = (0,) + cuts + (N,)
+        if any(sum(m[b[j]:b[j + 1]]) > M[j] for j in range(T)):
+            continue
+        worst = max(sum(f[b[j]:b[j + 1]]) / C[j] for j in range(T))
+        if worst < best:
+            best_p, best = list(cuts), worst
+    return best_p, best
 
 
 def tier_loads(p: Sequence[int], f, C) -> List[float]:
@@ -103,17 +121,14 @@ def tier_loads(p: Sequence[int], f, C) -> List[float]:
 
 
 def hypsched_rt(F_new: float, m_act: float, C, M_avail, available, F_run_rem, F_wait) -> Optional[int]:
-    """Algorithm 2 for one tier.  Per node k: capacity C[k], available memory M_avail[k],
-    availability flag, remaining workload of the running task, summed workload of the
-    waiting tasks.  Returns the index of k* or None."""
-    min_cost, k_star = float("inf"), None
-    for k in range(len(C)):
-        if available[k] and M_avail[k] >= m_act:
-            F_queued = F_run_rem[k] + F_wait[k]
-            cost = (F_queued + F_new) / C[k]
-            if cost < min_cost:
-                min_cost, k_star = cost, k
-    return k_star
+    """Algorithm 2 for one tier: k* = argmin over the eligible nodes of the expected completion
+    (F_run_rem,k + F_wait,k + F_new) / C_k  (the k* equation of Sec. IV-B); a node is eligible when it is
+    available and has m_act of memory free.  Ties go to the node listed first; no eligible node -> None."""
+    eligible = [k for k in range(len(C)) if available[k] and M_avail[k] >= m_act]
+    if not eligible:
+        return None
+    completion = {k: (F_run_rem[k] + F_wait[k] + F_new) / C[k] for k in eligible}
+    return min(eligible, key=lambda k: (completion[k], k))
 
 
 def simulate_tiers(arrivals: Sequence[float], F: Sequence[float], m_act: Sequence[float], C, M,

@@ -77,8 +77,7 @@ def test_feasibility_is_monotone_in_tau():
     assert tau_opt < math.inf
     seen_true = False
     for tau in np.linspace(0.0, 2.0 * tau_opt, 200):
-        DP, _ = op.p_check(float(tau), f, m, C, M)
-        ok = DP[3][10]
+        ok, _ = op.p_check(float(tau), f, m, C, M)
         assert ok == (tau >= tau_opt - 1e-12)
         assert not (seen_true and not ok)
         seen_true = seen_true or ok

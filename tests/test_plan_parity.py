@@ -50,6 +50,30 @@ def test_hypsplit_equals_oracle_bit_for_bit(seed):
     assert got_tau == want_tau  # same binary-search sequence, same doubles
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_hypsplit_against_the_plain_min_max_definition(seed):
+    """The library's planner against the optimisation problem itself, with no dynamic programme in
+    between: every partition vector of a small instance is tried (Sec. IV-A's objective and memory
+    constraint), and the library must return a feasible vector whose largest tier load is that
+    minimum, with tau* at most eps above it."""
+    rng = np.random.default_rng(5000 + seed)
+    N = int(rng.integers(2, 12))
+    T = int(rng.integers(1, min(N, 4) + 1))
+    f, m, C, M = _instance(rng, N, T, ("none", "tight", "short")[seed % 3])
+    eps = 1e-9
+    p_best, load_best = op.best_partition_by_enumeration(f, m, C, M)
+    p, tau = hyp.hypsplit_dp(f, m, C, M, eps)
+    if p_best is None:
+        assert p is None
+        return
+    assert p is not None
+    b = [0] + p + [N]
+    assert all(b[j] < b[j + 1] for j in range(T))
+    assert all(sum(m[b[j]:b[j + 1]]) <= M[j] for j in range(T))
+    assert max(op.tier_loads(p, f, C)) == pytest.approx(load_best, rel=1e-12)
+    assert -1e-12 <= tau - load_best <= eps + 1e-12
+
+
 def test_hypsplit_zero_cost_blocks_and_ties():
     # zero-cost blocks make many cuts equally good: the kept one must be the oracle's
     f = [0.0, 2.0, 0.0, 0.0, 2.0, 0.0, 2.0, 0.0]

@@ -46,7 +46,7 @@ def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE, ca
     starts = np.concatenate([[0], np.cumsum(lens)])
     rng = np.random.default_rng(seed)
     caches = {}
-    worst = 0.0
+    worst = worst_update = 0.0
     for b in sample_reqs:
         L = lens[b]
         xb = x[starts[b]: starts[b] + L]
@@ -56,8 +56,10 @@ def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE, ca
         g = got[starts[b]: starts[b] + L][rows]
         e = rel_err(g, ref)
         eu = rel_err(g - xb[rows], ref - xb[rows])
-        assert e <= TOL and eu <= TOL + 2.0 ** -8 * np.abs(ref).max() / np.abs(ref - xb[rows]).max(), (b, e, eu)
+        # the update (output - input) is held to the same bound, with no allowance for the bf16 rounding of the output
+        assert e <= TOL and eu <= TOL, (b, e, eu)
         worst = max(worst, e)
+        worst_update = max(worst_update, eu)
         # the cache the GPU built for this request, against the oracle's
         k, v = gst.export_kv(0, b)
         assert rel_err(to_host(k), Kc[:L]) <= TOL and rel_err(to_host(v), Vc[:L]) <= TOL
@@ -72,7 +74,7 @@ def check_requests(layer, lens, seed, sample_reqs, decode_steps, SHAPE=SHAPE, ca
             assert e <= TOL, (s, b, e)
             worst = max(worst, e)
     gst.destroy()
-    print(f"\nlens {lens[:4]}{'...' if len(lens) > 4 else ''} cap {cap}: worst rel err {worst:.3e}")
+    print(f"\nlens {lens[:4]}{'...' if len(lens) > 4 else ''} cap {cap}: worst rel err {worst:.3e}, of the prefill update {worst_update:.3e}")
     return worst
 
 

@@ -7,6 +7,8 @@ adds to its input (out - in), so that an error in the attention or FFN branch
 cannot hide behind the residual stream."""
 import dataclasses
 
+import os
+
 import numpy as np
 import pytest
 
@@ -24,10 +26,11 @@ def check(got, ref, x_in, dtype, what=""):
     e = rel_err(got, ref)
     assert e <= tol, f"{what}: rel err {e:.3e} > {tol}"
     upd = rel_err(got - x_in, ref - x_in)
-    # the bf16 output itself is rounded to 8 bits of mantissa: allow that rounding
-    # of the full-size value on top of the tolerance on the update
-    slack = 0.0 if dtype == "f32" else (2.0 ** -8) * np.abs(ref).max() / max(np.abs(ref - x_in).max(), 1e-30)
-    assert upd <= tol + slack, f"{what}: rel err of the update {upd:.3e} > {tol + slack:.3e}"
+    # the update a stage adds to its input is held to the same bound as the output, so a wrong
+    # attention or FFN branch cannot hide behind the residual; HYP_PRINT_ERRS=1 prints both
+    if os.environ.get("HYP_PRINT_ERRS"):
+        print(f"{what}: out {e:.3e} update {upd:.3e} (|update|max / |out|max = {np.abs(ref - x_in).max() / np.abs(ref).max():.3f})")
+    assert upd <= tol, f"{what}: rel err of the update {upd:.3e} > {tol}"
     return e
 
 

@@ -18,8 +18,9 @@ namespace {
 // W = P(N, K): the 1 KiB tiles of one 32-row block are contiguous along K and a
 // tile is the MFMA A fragment as it stands, so every wave streams its slice
 // with fully coalesced 1 KiB loads straight into registers.  x = P(32, K) is
-// tiny and stays in L2.  A workgroup owns 64 packed rows (2 blocks); its 4 waves
-// split the workgroup's K slice and are reduced through LDS in wave order; the
+// tiny and stays in L2.  A workgroup owns 64 packed rows (2 blocks; 32 rows in the
+// unsplit form of the O / down projections); its NW waves (4, 8 or 16) split the
+// workgroup's K slice and are reduced through LDS in wave order; the
 // `ksplit` workgroups of one row group (twice as many for the row groups that would
 // otherwise form a thin second round of the launch) write fp32 partial sums, and the one that
 // arrives last (a counter per row group) adds them up in slice order - so the
@@ -38,9 +39,9 @@ namespace {
 //              step's token into the cached lengths (every reader of them in this
 //              step ran in an earlier kernel)
 // ----------------------------------------------------------------------------
-// UNROLL k-tiles per batch: 10 weight loads of 1 KiB in flight per wave and 4 workgroups per
-// CU (124 registers) measured better than 20 in flight at 3 per CU
-constexpr int kWavesPerCu = 16;  // 4 per SIMD at 124 registers: NW waves per workgroup, kWavesPerCu / NW workgroups per CU
+// A wave keeps 10 weight loads of 1 KiB in flight (a window of 5 k-tiles of two row blocks, or 10 of
+// one); 16 such waves per CU (124 registers) measured better than 20 loads in flight at 12 waves.
+constexpr int kWavesPerCu = 16;  // 4 per SIMD: NW waves per workgroup, kWavesPerCu / NW workgroups per CU
 constexpr int kBeginRows = 64;  // rows per workgroup of the kernel that opens a step (and per sum of squares it writes)
 
 struct DecGemvParams {
@@ -114,9 +115,9 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
       if (idx < p.batch * 32) pos_pf[j] = p.lens[idx >> 5];
     }
   }
-  // the workgroup's four waves take the k-tiles of its slice in turn, so that each step of
-  // the workgroup reads 4 KiB contiguous per row block (HBM serves that pattern ~10 % faster
-  // than four separate 1 KiB streams)
+  // the workgroup's NW waves take the k-tiles of its slice in turn, so that each step of
+  // the workgroup reads NW KiB contiguous per row block (HBM serves that pattern ~10 % faster
+  // than separate 1 KiB streams)
   const int kt0 = ks * NW * tiles_per_wave + wave;
   constexpr size_t kStep = (size_t)NW * kTileElems;
   f32x16_t acc[FBW];

@@ -13,8 +13,17 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ __forceinline__ float xhalf_max(float v) { return fmaxf(v, __shfl_xor(v, 32, 64)); }
-__device__ __forceinline__ float xhalf_sum(float v) { return v + __shfl_xor(v, 32, 64); }
+// The two halves of a wave exchanged in the vector ALU (v_permlane32_swap: lanes 32..63 of its first operand
+// trade places with lanes 0..31 of its second), not through the LDS crossbar and its wait: with both operands v
+// the first result holds v's lower half in both halves, the second its upper half.
+struct HalfPair { float lo, hi; };
+__device__ __forceinline__ HalfPair both_halves(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+__device__ __forceinline__ float xhalf_max(float v) { const HalfPair h = both_halves(v); return fmaxf(h.lo, h.hi); }
+__device__ __forceinline__ float xhalf_sum(float v) { const HalfPair h = both_halves(v); return h.lo + h.hi; }
 
 __device__ __forceinline__ bf16x8_t probs_operand(const float *p /*16*/, int m) {
   // MFMA step m of the P V product contracts keys 16m + 8(e/4) + 4hh + e%4: registers 8m .. 8m+7
@@ -61,7 +70,9 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
                                                       const PrefillTile *__restrict__ tiles,
                                                       const int *__restrict__ req_len, int nq, int G) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hh = lane >> 5, tl = lane & 31;
+  // wave-uniform values in scalar registers: the LDS destination of a direct load has to be uniform, and a wave index
+  // the compiler takes for divergent turns every such load into a loop over lanes
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, hh = lane >> 5, tl = lane & 31;
   const int nw = blockDim.x >> 6;  // 2 G
   const PrefillTile tile = tiles[blockIdx.x];
   const int kvh = blockIdx.y;
@@ -159,7 +170,8 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
   // The scheduling-group builtins fix that interleaving; left alone the compiler bunches the MFMAs.
   bf16x8_t pf[4];
   int buf = 0;  // buffer of stage st
-  for (int st = 0; st + 1 < n_st; ++st) {
+  // one stage of the loop: consumes the scores c0, c1 of stage st, leaves those of stage st + 1 in n0, n1
+  auto stage = [&](int st, const f32x16_t &c0, const f32x16_t &c1, f32x16_t &n0, f32x16_t &n1) {
     const int buf1 = buf + 1 == kKvBufs ? 0 : buf + 1, buf2 = buf1 + 1 == kKvBufs ? 0 : buf1 + 1;
     if (st + 2 < n_st) issue(off_next, buf2);  // over stage st - 1, which every wave has left
     // Fragments come from LDS in batches of four, each batch requested one group of four MFMAs ahead
@@ -176,7 +188,6 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
     follow_max(mx);
     const float mc = m_run * c;
     // ---- phase 1: scores of stage st + 1 | probabilities of stage st
-    f32x16_t n0, n1;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { n0[r] = 0.f; n1[r] = 0.f; }
     float p[32];
@@ -194,8 +205,8 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
       // two probabilities and their rounding per MFMA: registers 2 i and 2 i + 1 of the 32 scores
       {
         const int r0 = 2 * i, r1 = 2 * i + 1;
-        p[r0] = fast_exp2((r0 < 16 ? s0[r0] : s1[r0 - 16]) * c - mc);
-        p[r1] = fast_exp2((r1 < 16 ? s0[r1] : s1[r1 - 16]) * c - mc);
+        p[r0] = fast_exp2((r0 < 16 ? c0[r0] : c1[r0 - 16]) * c - mc);
+        p[r1] = fast_exp2((r1 < 16 ? c0[r1] : c1[r1 - 16]) * c - mc);
         pf[r0 >> 3][r0 & 7] = (__bf16)p[r0];
         pf[r0 >> 3][r1 & 7] = (__bf16)p[r1];
       }
@@ -216,16 +227,33 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
       rowsum += p[2 * i];
       rowsum += p[2 * i + 1];
       mx = max3(mx, n0[i], n1[i]);
+      // an empty statement that "uses" both: without it the two chains are sunk as a whole below the loop's last
+      // MFMA (they are only needed there), and the matrix pipe runs phase 2 alone
+      asm volatile("" : "+v"(rowsum), "+v"(mx));
       __builtin_amdgcn_sched_barrier(0);
     }
     l_run += rowsum;
-    s0 = n0; s1 = n1;
     buf = buf1;
     // a paged cache answers this with a scalar load; issued here, it completes under the wait below -
     // outstanding during the phases it would turn every LDS wait into a full one
     off_next = stage_off(st + 3);
     __builtin_amdgcn_s_waitcnt(0x0070);  // my loads of stage st + 2 landed, my LDS reads of stage st done
     __syncthreads();
+  };
+  // two stages per trip with the roles of the two accumulator pairs swapped, so that no stage ends by copying
+  // the next scores into the current ones; an odd stage count starts with a single stage (one copy per tile)
+  {
+    f32x16_t t0, t1;
+    int st = 0;
+    if ((n_st - 1) & 1) {
+      stage(0, s0, s1, t0, t1);
+      s0 = t0; s1 = t1;
+      st = 1;
+    }
+    for (; st + 1 < n_st; st += 2) {
+      stage(st, s0, s1, t0, t1);
+      stage(st + 1, t0, t1, s0, s1);
+    }
   }
   // last stage: the only one that touches the diagonal (a block past the tile's need is fully
   // masked here: its keys lie after every row)

@@ -63,17 +63,18 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // Not inline assembly: the compiler's hazard logic must see that the operands come out of MFMAs.
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-__global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__ q,
+template <int G>
+__global__ void __launch_bounds__(128 * G) k_attn_prefill(const bf16_t *__restrict__ q,
                                                       const bf16_t *__restrict__ Kc,
                                                       const bf16_t *__restrict__ Vc, CacheGeom geom,
                                                       bf16_t *__restrict__ out,
                                                       const PrefillTile *__restrict__ tiles,
-                                                      const int *__restrict__ req_len, int nq, int G) {
+                                                      const int *__restrict__ req_len, int nq) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   // wave-uniform values in scalar registers: the LDS destination of a direct load has to be uniform, and a wave index
   // the compiler takes for divergent turns every such load into a loop over lanes
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, hh = lane >> 5, tl = lane & 31;
-  const int nw = blockDim.x >> 6;  // 2 G
+  constexpr int nw = 2 * G;  // waves per workgroup
   const PrefillTile tile = tiles[blockIdx.x];
   const int kvh = blockIdx.y;
   const int head = kvh * G + (wave >> 1);
@@ -107,9 +108,21 @@ __global__ void __launch_bounds__(512) k_attn_prefill(const bf16_t *__restrict__
   auto issue = [&](size_t off, int buf) {
     // 32 tiles of 1 KiB: [key block 0: 8 K, 8 V][key block 1: 8 K, 8 V]; the second
     // block of the last stage may lie past the tile's need but is inside the cache
-    for (int t = wave; t < 32; t += nw) {
-      const bf16_t *src = ((t & 8) ? Vc : Kc) + off + (size_t)(t >> 4) * (32 * 128) + (size_t)(t & 7) * kTileElems + lane * 8;
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvStageBytes + t * 1024), 16, 0, 0);
+    // wave w fetches tiles w, w + nw, ...; with 2, 4 or 8 waves everything about a tile but w itself is known at
+    // compile time, and the loop unrolls into straight scalar address arithmetic
+    if constexpr (nw == 2 || nw == 4 || nw == 8) {
+      constexpr int per8 = 8 / nw;
+#pragma unroll
+      for (int j = 0; j < 32 / nw; ++j) {
+        const int hi = j / per8, lo = nw * (j % per8);  // tile t = 8 hi + lo + wave
+        const bf16_t *src = ((hi & 1) ? Vc : Kc) + off + (size_t)(hi >> 1) * (32 * 128) + (size_t)(lo + wave) * kTileElems + lane * 8;
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvStageBytes + (8 * hi + lo + wave) * 1024), 16, 0, 0);
+      }
+    } else {
+      for (int t = wave; t < 32; t += nw) {
+        const bf16_t *src = ((t & 8) ? Vc : Kc) + off + (size_t)(t >> 4) * (32 * 128) + (size_t)(t & 7) * kTileElems + lane * 8;
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t *)src, (lds_ptr_t *)(lds + buf * kKvStageBytes + t * 1024), 16, 0, 0);
+      }
     }
   };
   // scores of both 32-key blocks of the stage in `buf`: two independent accumulator chains
@@ -499,13 +512,24 @@ hipError_t mfma_attn_prefill(const bf16_t *q, const bf16_t *Kc, const bf16_t *Vc
                              bf16_t *out, const PrefillTile *tiles, int n_tiles, const int *req_len,
                              int nq, int nkv, hipStream_t s) {
   if (n_tiles == 0) return hipSuccess;
-  int G = nq / nkv;
-  k_attn_prefill<<<dim3(n_tiles, nkv), 2 * G * 64, kAttnPrefillLds, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq, G);
+  const int G = nq / nkv;
+  const dim3 grid(n_tiles, nkv);
+  switch (G) {
+    case 1: k_attn_prefill<1><<<grid, 128, kAttnPrefillLds, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq); break;
+    case 2: k_attn_prefill<2><<<grid, 256, kAttnPrefillLds, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq); break;
+    case 3: k_attn_prefill<3><<<grid, 384, kAttnPrefillLds, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq); break;
+    case 4: k_attn_prefill<4><<<grid, 512, kAttnPrefillLds, s>>>(q, Kc, Vc, geom, out, tiles, req_len, nq); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 
 hipError_t mfma_attn_init() {
-  return hipFuncSetAttribute((const void *)k_attn_prefill, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnPrefillLds);
+  hipError_t e = hipFuncSetAttribute((const void *)k_attn_prefill<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnPrefillLds);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_attn_prefill<2>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnPrefillLds);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_attn_prefill<3>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnPrefillLds);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_attn_prefill<4>, hipFuncAttributeMaxDynamicSharedMemorySize, kAttnPrefillLds);
+  return e;
 }
 
 size_t mfma_attn_decode_part_floats(int nq, int batch, int max_chunks) {

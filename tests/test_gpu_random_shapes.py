@@ -1,5 +1,5 @@
 """Seeded random sweep over what the fixed parity cases leave between them: head groupings
-(1, 2, 4 query heads per KV head), widths, stage depths, batch widths up to 32, prompt
+(1 - 4 query heads per KV head), widths, stage depths, batch widths up to 32, prompt
 lengths on and off the 32 / 64 / 128 boundaries, slab and shuffled-page caches, capacity
 with and without slack.  Every case runs the MFMA stage through the C ABI against the CPU
 oracle (Sec. III-A block, Eq. 1 stacking), whole tensors, prefill + decode steps, 2e-2."""
@@ -18,7 +18,7 @@ N_CASES = 24
 def draw_case(i):
     rng = np.random.default_rng(77_000 + i)
     n_kv = int(rng.choice([2, 4]))
-    G = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 4]))
     hidden = int(rng.choice([256, 512, 768]))
     ffn = int(rng.choice([256, 512, 768, 1280]))
     shape = synth.BlockShape(hidden=hidden, n_q_heads=G * n_kv, n_kv_heads=n_kv, head_dim=128, ffn_dim=ffn, dtype="bf16")

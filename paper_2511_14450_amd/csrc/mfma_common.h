@@ -39,13 +39,15 @@ __host__ __device__ inline size_t frag_offset(size_t row, size_t k, size_t K) {
 }
 
 // The fp32 residual stream of a prefill is kept in *accumulator order*, "A(T', H)":
-// blocks of 32 tokens x 32 features of 4 KiB, stored as 4 groups g of 64 lanes x 4
-// floats - lane l of group g holds token l % 32, features 8g + 4(l/32) + 0..3, i.e.
-// registers 4g .. 4g+3 of that lane's accumulator block.  A GEMM epilogue then reads
-// and writes the residual with 1 KiB contiguous wave accesses.
+// blocks of 32 tokens x 32 features of 4 KiB, stored as 4 groups [fh][th] (feature half,
+// token half) of 64 lanes x 4 floats - lane l of group [fh][th] holds token 16 th + l % 16,
+// features 16 fh + 4 (l / 16) + 0..3, i.e. the four registers of that lane's 16 x 16 MFMA
+// output [fh][th] of the block.  A GEMM epilogue then reads and writes the residual with
+// 1 KiB contiguous wave accesses.
 __host__ __device__ inline size_t acc_offset(size_t row, size_t col, size_t H) {
-  size_t f = col & 31;
-  return (((row >> 5) * (H >> 5) + (col >> 5)) * 4 + (f >> 3)) * 256 + ((((f >> 2) & 1) << 5) + (row & 31)) * 4 + (f & 3);
+  const size_t f = col & 31, t = row & 31;
+  const size_t group = ((f >> 4) << 1) | (t >> 4), lane = (((f >> 2) & 3) << 4) | (t & 15);
+  return (((row >> 5) * (H >> 5) + (col >> 5)) * 4 + group) * 256 + lane * 4 + (f & 3);
 }
 
 // Value tile of the KV cache: 32 feature rows (d) x 16 keys, contraction over

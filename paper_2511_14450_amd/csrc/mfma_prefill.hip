@@ -2,6 +2,7 @@
 // at the two ends of the residual stream, the LDS-staged GEMM with its four
 // epilogues (RoPE + KV-cache write, SwiGLU, residual add + next RMS Norm's gain
 // and statistics, plain), for the decoder block of Sec. III-A.
+#include <type_traits>
 #include "mfma_common.h"
 #include "mfma_kernels.h"
 
@@ -135,14 +136,18 @@ __global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part
 // GEMM  C^T[N, T] = W[N, K] X[T, K]^T  on fragment-order operands.
 //
 // Workgroup tile 256 features x 256 tokens, 8 waves (4 along features x 2 along
-// tokens), each wave 2 x 4 accumulator blocks of 32x32 (128 fp32 registers).
-// K advances in stages of 32 (2 k-tiles); 4 stages of 32 KiB rotate through LDS
-// and are filled by direct global->LDS wave loads issued three stages ahead, 4
-// per wave and stage.  Fragments are read from LDS with linear, conflict-free
-// ds_read_b128 one k-tile ahead of the MFMAs that use them.  Every LDS read and
-// every global->LDS load is pinned behind one particular MFMA of the k-tile (reads
-// after the first six, loads after every second one): left to the compiler they
-// bunch up and the matrix pipe waits for the burst to issue.
+// tokens), each wave 64 x 128 = 2 x 4 blocks of 32 x 32, every block four 16 x 16
+// outputs of v_mfma_f32_16x16x32_bf16 (128 fp32 registers).  That shape, not
+// 32x32x16: on Gaussian operands the chip sustains 2.06 PFLOP/s of it from registers
+// against 1.78 of the 32x32x16 form (it is power-limited, and the deeper, narrower
+// product costs less per FLOP), and this kernel got 6 - 8 % faster by the change.
+// K advances in stages of 32 (2 k-tiles = one MFMA's depth); 4 stages of 32 KiB rotate
+// through LDS and are filled by direct global->LDS wave loads issued three stages
+// ahead, 4 per wave and stage.  Fragments are read from LDS with conflict-free
+// ds_read_b128 (16 lanes on 256 contiguous bytes) well ahead of the MFMAs that use
+// them.  Every LDS read and every global->LDS load is pinned behind one particular
+// MFMA of the stage: left to the compiler they bunch up and the matrix pipe waits
+// for the burst to issue.
 // One barrier per stage.  Workgroups are numbered so that the ones
 // that run together on an XCD (id % 8) cover a band of `gm` token tiles times
 // consecutive feature tiles and share operand panels in that XCD's L2.
@@ -181,15 +186,15 @@ struct GemmParams {
   unsigned *split_counters;
 };
 
-__device__ __forceinline__ void store_block(bf16_t *out, int out_K, int tb, int f0, int lane,
-                                            const float *v /*16*/) {
-  // 32 features [f0, f0+32) x 32 tokens of block tb into P(T', out_K)
-  int hh = lane >> 5, t = lane & 31;
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    size_t off = ((size_t)tb * (out_K >> 4) + ((f0 + 8 * g) >> 4)) * kTileElems + (((g & 1) << 5) + t) * 8 + hh * 4;
-    *(bf16x4_t *)(out + off) = pack4(v[4 * g], v[4 * g + 1], v[4 * g + 2], v[4 * g + 3]);
-  }
+// Accumulators.  A wave's 32 x 32 block (features x tokens) is four 16 x 16 outputs of v_mfma_f32_16x16x32_bf16,
+// indexed [fh][th] (feature half, token half); lane l holds, in the four registers e of output [fh][th],
+// features 16 fh + 4 (l / 16) + e of token 16 th + l % 16.
+struct AccLane {
+  int q, t16;  // l / 16, l % 16
+};
+// four consecutive features f0 .. f0+3 (f0 a multiple of 4) of internal row `row` into P(T', out_K): one 8-byte store
+__device__ __forceinline__ void store4(bf16_t *out, int out_K, int row, int f0, f32x4_t v) {
+  *(bf16x4_t *)(out + frag_offset(row, f0, out_K)) = pack4(v[0], v[1], v[2], v[3]);
 }
 
 // CLS (a hyp_kernel_class_t) does not change the code: it gives each GEMM of a block a kernel name of its
@@ -213,13 +218,17 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
   const int tb0 = tile_t * XB, nb0 = tile_n * NBK;
   const int KT = p.KT;
 
-  f32x16_t acc[FB][TB];
+  f32x4_t acc[FB][2][TB][2];  // [feature block][feature half][token block][token half]
 #pragma unroll
   for (int i = 0; i < FB; ++i)
 #pragma unroll
-    for (int j = 0; j < TB; ++j)
+    for (int fh = 0; fh < 2; ++fh)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int j = 0; j < TB; ++j)
+#pragma unroll
+        for (int th = 0; th < 2; ++th)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][fh][j][th][e] = 0.f;
 
   const int nsteps = KT / KTS / p.ksplit;  // stages of this workgroup's K slice, >= NST guaranteed by the host
   const size_t k_first = (size_t)slice * nsteps * KTS * kTileElems;
@@ -246,77 +255,98 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (((NST - 1) * LPW) & 15) | ((((NST - 1) * LPW) >> 4) << 14));
   __builtin_amdgcn_s_barrier();
 
-  bf16x8_t wfr[2][FB], xfr[2][TB];
-  auto readfr = [&](int which, int buf, int kt) {
-    const char *base = lds + buf * STAGE_BYTES + lane * 16;
-#pragma unroll
-    for (int i = 0; i < FB; ++i) wfr[which][i] = *(const bf16x8_t *)(base + ((XB + wf * FB + i) * KTS + kt) * 1024);
-#pragma unroll
-    for (int i = 0; i < TB; ++i) xfr[which][i] = *(const bf16x8_t *)(base + ((wt * TB + i) * KTS + kt) * 1024);
+  // Fragments.  A stage holds, per 32-row block, its two k-tiles back to back (2 KiB); the operand of a
+  // 16x16x32 MFMA for rows 16 h .. 16 h + 15 of the block takes from lane l rows' 16 bytes k-chunk l / 16 of
+  // row 16 h + l % 16: byte (l / 16) * 512 + h * 256 + (l % 16) * 16 of the block - 16 lanes read 256 contiguous
+  // bytes, no bank conflicts.  The four feature fragments of a stage (a = 2 i + fh) stay in registers for the
+  // whole stage (double-buffered); the eight token fragments (b = 2 j + th) pass through four slots, each read
+  // three groups of four MFMAs ahead of its use.
+  const char *frag_base = lds + (lane >> 4) * 512 + (lane & 15) * 16;
+  bf16x8_t afr[2][2 * FB], bfr[4];
+  auto read_a = [&](int which, int buf, int a) {
+    afr[which][a] = *(const bf16x8_t *)(frag_base + buf * STAGE_BYTES + (XB + wf * FB + (a >> 1)) * (KTS * 1024) + (a & 1) * 256);
   };
-  auto readfr1 = [&](int which, int buf, int kt, int m) {  // fragment m of FB + TB: one read in the shadow of one MFMA
-    const char *base = lds + buf * STAGE_BYTES + lane * 16;
-    if (m < FB) wfr[which][m] = *(const bf16x8_t *)(base + ((XB + wf * FB + m) * KTS + kt) * 1024);
-    else xfr[which][m - FB] = *(const bf16x8_t *)(base + ((wt * TB + (m - FB)) * KTS + kt) * 1024);
+  auto read_b = [&](int buf, int b) {
+    bfr[b & 3] = *(const bf16x8_t *)(frag_base + buf * STAGE_BYTES + (wt * TB + (b >> 1)) * (KTS * 1024) + (b & 1) * 256);
   };
-  readfr(0, 0, 0);
+  auto mfma_group = [&](int which, int b, int a) {
+    acc[a >> 1][a & 1][b >> 1][b & 1] =
+        __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[which][a], bfr[b & 3], acc[a >> 1][a & 1][b >> 1][b & 1], 0, 0, 0);
+  };
+#pragma unroll
+  for (int a = 0; a < 2 * FB; ++a) read_a(0, 0, a);
+#pragma unroll
+  for (int b = 0; b < 3; ++b) read_b(0, b);
   int buf = 0;
-  for (int s = 0; s + 1 < nsteps; ++s) {
-    int nbuf = buf + 1 == NST ? 0 : buf + 1;
-    int lstep = s + NST < nsteps ? s + NST : nsteps - 1;  // tail refills land in buffers nobody reads again
+  // One stage = 8 groups (token fragments b) of 4 MFMAs (feature fragments a).  Groups 0 - 4 each request the
+  // token fragment three groups ahead; then every LDS read of the stage is out, the barrier says stage s + 1 has
+  // landed everywhere, and groups 5 - 7 request the next stage's feature fragments and first three token fragments
+  // and refill this stage's buffer - every request pinned behind one particular MFMA.
+  auto stage = [&](auto cur_tag, int s) {
+    constexpr int cur = decltype(cur_tag)::value, nxt = cur ^ 1;
+    const int nbuf = buf + 1 == NST ? 0 : buf + 1;
+    const int lstep = s + NST < nsteps ? s + NST : nsteps - 1;  // tail refills land in buffers nobody reads again
 #pragma unroll
-    for (int kt = 0; kt < KTS; ++kt) {
-      const int c = kt & 1, n = c ^ 1;
-      if (kt == KTS - 1) {
+    for (int b = 0; b < 2 * TB; ++b) {
+      if (b == 5) {
         // my part of stage s+1 has landed and all my LDS reads of stage s are done
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0x0070 | (((NST - 2) * LPW) & 15) | ((((NST - 2) * LPW) >> 4) << 14));
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
-        for (int i = 0; i < FB; ++i)
-#pragma unroll
-          for (int j = 0; j < TB; ++j) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
-            if (i * TB + j < FB + TB) {
-              __builtin_amdgcn_sched_barrier(0);
-              readfr1(n, nbuf, 0, i * TB + j);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-            if (((i * TB + j) & 1) == 0 && ((i * TB + j) >> 1) < LPW) {
-              issue1((i * TB + j) >> 1, lstep, buf);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
-      } else {
+      for (int a = 0; a < 2 * FB; ++a) {
+        mfma_group(cur, b, a);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < FB; ++i)
-#pragma unroll
-          for (int j = 0; j < TB; ++j) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
-            if (i * TB + j < FB + TB) {
-              __builtin_amdgcn_sched_barrier(0);
-              readfr1(n, buf, kt + 1, i * TB + j);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
+        if (b < 5) {
+          if (a == 0) read_b(buf, b + 3);
+        } else {
+          const int m = (b - 5) * 4 + a;  // 0 .. 11 behind the barrier
+          if (m == 0) read_a(nxt, nbuf, 0);
+          if (m == 1) issue1(0, lstep, buf);
+          if (m == 2) read_a(nxt, nbuf, 1);
+          if (m == 3) read_b(nbuf, 0);      // slot 0 held fragment 4
+          if (m == 4) read_a(nxt, nbuf, 2);
+          if (m == 5) issue1(1, lstep, buf);
+          if (m == 6) read_a(nxt, nbuf, 3);
+          if (m == 7) read_b(nbuf, 1);      // slot 1 held fragment 5
+          if (m == 8) issue1(2, lstep, buf);
+          if (m == 9) read_b(nbuf, 2);      // slot 2 held fragment 6
+          if (m == 10) issue1(3, lstep, buf);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     buf = nbuf;
-  }
+  };
+  static_assert(LPW == 4 && FB == 2 && TB == 4, "the pinned slots above assume 4 loads, 4 + 8 fragments per stage");
+  // Stages run in pairs (the feature fragments alternate between two register sets); an odd count starts with a
+  // single stage and one copy of its set.  The very last stage requests nothing beyond itself.
+  {
+    int s = 0;
+    if (nsteps & 1) {
+      stage(std::integral_constant<int, 0>(), 0);
 #pragma unroll
-  for (int kt = 0; kt < KTS; ++kt) {
-    const int c = kt & 1, n = c ^ 1;
-    if (kt + 1 < KTS) readfr(n, buf, kt + 1);
+      for (int a = 0; a < 2 * FB; ++a) afr[0][a] = afr[1][a];
+      s = 1;
+    }
+    for (; s + 2 < nsteps; s += 2) {
+      stage(std::integral_constant<int, 0>(), s);
+      stage(std::integral_constant<int, 1>(), s + 1);
+    }
+    stage(std::integral_constant<int, 0>(), s);
 #pragma unroll
-    for (int i = 0; i < FB; ++i)
+    for (int b = 0; b < 2 * TB; ++b)
 #pragma unroll
-      for (int j = 0; j < TB; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[c][i], xfr[c][j], acc[i][j], 0, 0, 0);
+      for (int a = 0; a < 2 * FB; ++a) {
+        mfma_group(1, b, a);
+        if (a == 0 && b < 5) read_b(buf, b + 3);
+      }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);  // drain the tail refills before the wave ends
 
+  constexpr int kAccRegs = FB * 2 * TB * 2 * 4;  // 128
   // ------------------------------------------------------------------ split K: the last workgroup of a tile adds up
   if (p.ksplit > 1) {
     // Every workgroup of a tile leaves its fp32 accumulators of the live token blocks in the
@@ -324,15 +354,18 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     // that arrives last reads all slices back in slice order - so the sum does not depend on
     // which one that is - and goes on to the epilogue.  Plain loads suffice: every line has one
     // writer in this launch and no reader before the counter says so.
-    float *mine = p.split_ws + (((size_t)q * p.ksplit + slice) * (WF * WT) + wave) * (FB * TB * 16 * 64);
+    float *mine = p.split_ws + (((size_t)q * p.ksplit + slice) * (WF * WT) + wave) * (kAccRegs * 64);
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
       if (tb0 + wt * TB + j >= p.tok_blocks) continue;
 #pragma unroll
       for (int i = 0; i < FB; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          __hip_atomic_store(mine + ((i * TB + j) * 16 + r) * 64 + lane, acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            __hip_atomic_store(mine + (((i * TB + j) * 4 + h) * 4 + e) * 64 + lane, acc[i][h >> 1][j][h & 1][e], __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -343,14 +376,14 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     }
     __syncthreads();
     if (!split_last) return;
-    const float *tile_ws = p.split_ws + ((size_t)q * p.ksplit * (WF * WT) + wave) * (FB * TB * 16 * 64);
-    const size_t slice_stride = (size_t)(WF * WT) * (FB * TB * 16 * 64);
+    const float *tile_ws = p.split_ws + ((size_t)q * p.ksplit * (WF * WT) + wave) * (kAccRegs * 64);
+    const size_t slice_stride = (size_t)(WF * WT) * (kAccRegs * 64);
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
       if (tb0 + wt * TB + j >= p.tok_blocks) continue;
 #pragma unroll
       for (int i = 0; i < FB; ++i) {
-        f32x16_t sum;
+        float sum[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) sum[r] = 0.f;
         for (int s0 = 0; s0 < p.ksplit; s0 += 4) {  // 4 slices x 16 values in flight
@@ -365,25 +398,27 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) sum[r] += v[u][r];
         }
-        acc[i][j] = sum;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][(r >> 3) & 1][j][(r >> 2) & 1][r & 3] = sum[r];
       }
     }
   }
 
   // ------------------------------------------------------------------ epilogue
-  const int hh = lane >> 5, tl = lane & 31;
+  // lane l: features 4 q .. 4 q + 3 of a 16-feature half, token t16 of a 16-token half
+  const int q4 = (lane >> 4) * 4, t16 = lane & 15;
   if (EPI == EPI_STORE) {
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
       int tb = tb0 + wt * TB + j;
       if (tb >= p.tok_blocks) continue;
 #pragma unroll
-      for (int i = 0; i < FB; ++i) {
-        float v[16];
+      for (int i = 0; i < FB; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) v[r] = acc[i][j][r];
-        store_block(p.out, p.out_K, tb, (nb0 + wf * FB + i) * 32, lane, v);
-      }
+        for (int fh = 0; fh < 2; ++fh)
+#pragma unroll
+          for (int th = 0; th < 2; ++th)
+            store4(p.out, p.out_K, tb * 32 + 16 * th + t16, (nb0 + wf * FB + i) * 32 + 16 * fh + q4, acc[i][fh][j][th]);
     }
   } else if (EPI == EPI_SWIGLU) {
     // block 0 = gate, block 1 = up of FFN features [(tile_n*4 + wf)*32, +32)
@@ -391,14 +426,21 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     for (int j = 0; j < TB; ++j) {
       int tb = tb0 + wt * TB + j;
       if (tb >= p.tok_blocks) continue;
-      const float rs = p.rstd[tb * 32 + tl];  // the input rows carry gain only: W (x g r) = r W (x g)
-      float v[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float g = acc[0][j][r] * rs, u = acc[1][j][r] * rs;
-        v[r] = g / (1.0f + __expf(-g)) * u;
+      for (int th = 0; th < 2; ++th) {
+        const int row = tb * 32 + 16 * th + t16;
+        const float rs = p.rstd[row];  // the input rows carry gain only: W (x g r) = r W (x g)
+#pragma unroll
+        for (int fh = 0; fh < 2; ++fh) {
+          f32x4_t v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float g = acc[0][fh][j][th][e] * rs, u = acc[1][fh][j][th][e] * rs;
+            v[e] = g / (1.0f + __expf(-g)) * u;
+          }
+          store4(p.out, p.out_K, row, (tile_n * 4 + wf) * 32 + 16 * fh + q4, v);
+        }
       }
-      store_block(p.out, p.out_K, tb, (tile_n * 4 + wf) * 32, lane, v);
     }
   } else if (EPI == EPI_RESID) {
     // x += W a ; y' = x * gain of the next norm ; sum of squares of these 64 features per token.
@@ -407,32 +449,37 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     for (int j = 0; j < TB; ++j) {
       int tb = tb0 + wt * TB + j;
       if (tb >= p.tok_blocks) continue;
-      const int row = tb * 32 + tl;
-      const bool live = p.row_ext[row] >= 0;
-      float ss = 0.f;
 #pragma unroll
-      for (int i = 0; i < FB; ++i) {
-        const int fb = nb0 + wf * FB + i;
-        float *xb = p.xres + ((size_t)tb * p.feat_blocks + fb) * 1024 + lane * 4;
-        float v[16];
+      for (int th = 0; th < 2; ++th) {
+        const int row = tb * 32 + 16 * th + t16;
+        const bool live = p.row_ext[row] >= 0;
+        float ss = 0.f;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          f32x4_t old = *(const f32x4_t *)(xb + g * 256);
-          bf16x4_t gg = *(const bf16x4_t *)(p.gain + fb * 32 + 8 * g + 4 * hh);
-          f32x4_t nw;
+        for (int i = 0; i < FB; ++i) {
+          const int fb = nb0 + wf * FB + i;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float xn = live ? old[e] + acc[i][j][4 * g + e] : 0.f;
-            nw[e] = xn;
-            ss += xn * xn;
-            v[4 * g + e] = xn * bf16_to_f32(gg.v[e]);
+          for (int fh = 0; fh < 2; ++fh) {
+            // the residual stream's accumulator order: group [fh][th] of the block, 64 lanes x 4 floats
+            float *xb = p.xres + (((size_t)tb * p.feat_blocks + fb) * 4 + fh * 2 + th) * 256 + lane * 4;
+            f32x4_t old = *(const f32x4_t *)xb;
+            bf16x4_t gg = *(const bf16x4_t *)(p.gain + fb * 32 + 16 * fh + q4);
+            f32x4_t nw, v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float xn = live ? old[e] + acc[i][fh][j][th][e] : 0.f;
+              nw[e] = xn;
+              ss += xn * xn;
+              v[e] = xn * bf16_to_f32(gg.v[e]);
+            }
+            *(f32x4_t *)xb = nw;
+            store4(p.out, p.out_K, row, fb * 32 + 16 * fh + q4, v);
           }
-          *(f32x4_t *)(xb + g * 256) = nw;
         }
-        store_block(p.out, p.out_K, tb, fb * 32, lane, v);
+        // the token's 64 features of this wave sit in the four lanes l % 16 == t16
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (lane < 16) p.ssq_part[(size_t)((nb0 + wf * FB) >> 1) * (p.tok_blocks * 32) + row] = ss;
       }
-      ss += __shfl_xor(ss, 32, 64);
-      if (hh == 0) p.ssq_part[(size_t)((nb0 + wf * FB) >> 1) * (p.tok_blocks * 32) + row] = ss;
     }
   } else {  // EPI_QKV
     const int n0 = tile_n * 256;              // first packed row of this tile
@@ -441,51 +488,52 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     for (int j = 0; j < TB; ++j) {
       int tb = tb0 + wt * TB + j;
       if (tb >= p.tok_blocks) continue;
-      int row = tb * 32 + tl;
-      int pos = p.row_pos[row], req = p.row_req[row];
-      const float rs = p.rstd[row];
-      if (n0 < p.qd + p.kvd) {
-        // q or k: rotate the pair (d, d + 64) by the angle of this position
-        float lo[16], hi[16];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          f32x4_t c4 = *(const f32x4_t *)(p.cos_tab + (size_t)pos * 64 + ib + 8 * g + 4 * hh);
-          f32x4_t s4 = *(const f32x4_t *)(p.sin_tab + (size_t)pos * 64 + ib + 8 * g + 4 * hh);
+      for (int th = 0; th < 2; ++th) {
+        const int row = tb * 32 + 16 * th + t16;
+        const int pos = p.row_pos[row], req = p.row_req[row];
+        const float rs = p.rstd[row];
+        if (n0 < p.qd + p.kvd) {
+          // q or k: rotate the pair (d, d + 64) by the angle of this position; block 0 holds d, block 1 d + 64
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float a = acc[0][j][4 * g + e] * rs, b = acc[1][j][4 * g + e] * rs;
-            lo[4 * g + e] = a * c4[e] - b * s4[e];
-            hi[4 * g + e] = b * c4[e] + a * s4[e];
+          for (int fh = 0; fh < 2; ++fh) {
+            const int d0 = ib + 16 * fh + q4;  // d0 .. d0 + 3 and their partners d0 + 64 ..
+            f32x4_t c4 = *(const f32x4_t *)(p.cos_tab + (size_t)pos * 64 + d0);
+            f32x4_t s4 = *(const f32x4_t *)(p.sin_tab + (size_t)pos * 64 + d0);
+            f32x4_t lo, hi;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float a = acc[0][fh][j][th][e] * rs, b = acc[1][fh][j][th][e] * rs;
+              lo[e] = a * c4[e] - b * s4[e];
+              hi[e] = b * c4[e] + a * s4[e];
+            }
+            if (n0 < p.qd) {
+              const int head = (n0 >> 7) + head_in_tile;
+              store4(p.out, p.out_K, row, head * 128 + d0, lo);
+              store4(p.out, p.out_K, row, head * 128 + 64 + d0, hi);
+            } else {
+              const int kvh = ((n0 - p.qd) >> 7) + head_in_tile;
+              bf16_t *kb = p.Kc + p.geom.off(req, kvh, pos >> 5);  // P(32, 128) of this key block
+              *(bf16x4_t *)(kb + frag_offset(pos & 31, d0, 128)) = pack4(lo[0], lo[1], lo[2], lo[3]);
+              *(bf16x4_t *)(kb + frag_offset(pos & 31, 64 + d0, 128)) = pack4(hi[0], hi[1], hi[2], hi[3]);
+            }
           }
-        }
-        if (n0 < p.qd) {
-          int head = (n0 >> 7) + head_in_tile;
-          store_block(p.out, p.out_K, tb, head * 128 + ib, lane, lo);
-          store_block(p.out, p.out_K, tb, head * 128 + 64 + ib, lane, hi);
         } else {
-          int kvh = ((n0 - p.qd) >> 7) + head_in_tile;
-          bf16_t *kb = p.Kc + p.geom.off(req, kvh, pos >> 5);  // P(32, 128) of this key block
+          // v: feature d of kv head, key `pos` -> value tile slot
+          const int kvh = ((n0 - p.qd - p.kvd) >> 7) + head_in_tile;
+          bf16_t *vb = p.Vc + p.geom.off(req, kvh, pos >> 5);
+          int m, khh;
+          const int e = vtile_slot_of_key(pos & 31, &m, &khh);
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            size_t o0 = (size_t)((ib + 8 * g) >> 4) * kTileElems + (((g & 1) << 5) + (pos & 31)) * 8 + hh * 4;
-            size_t o1 = (size_t)((64 + ib + 8 * g) >> 4) * kTileElems + (((g & 1) << 5) + (pos & 31)) * 8 + hh * 4;
-            *(bf16x4_t *)(kb + o0) = pack4(lo[4 * g], lo[4 * g + 1], lo[4 * g + 2], lo[4 * g + 3]);
-            *(bf16x4_t *)(kb + o1) = pack4(hi[4 * g], hi[4 * g + 1], hi[4 * g + 2], hi[4 * g + 3]);
-          }
+          for (int i = 0; i < FB; ++i)
+#pragma unroll
+            for (int fh = 0; fh < 2; ++fh)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const int d = ib + i * 64 + 16 * fh + q4 + r;
+                vb[(size_t)(m * 4 + (d >> 5)) * kTileElems + (khh * 32 + (d & 31)) * 8 + e] = f2bf_dev(acc[i][fh][j][th][r] * rs);
+              }
         }
-      } else {
-        // v: feature d of kv head, key `pos` -> value tile slot
-        int kvh = ((n0 - p.qd - p.kvd) >> 7) + head_in_tile;
-        bf16_t *vb = p.Vc + p.geom.off(req, kvh, pos >> 5);
-        int m, khh;
-        int e = vtile_slot_of_key(pos & 31, &m, &khh);
-#pragma unroll
-        for (int i = 0; i < FB; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            int d = ib + i * 64 + 8 * (r >> 2) + 4 * hh + (r & 3);
-            vb[(size_t)(m * 4 + (d >> 5)) * kTileElems + (khh * 32 + (d & 31)) * 8 + e] = f2bf_dev(acc[i][j][r] * rs);
-          }
       }
     }
   }

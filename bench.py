@@ -378,8 +378,9 @@ def main():
         # registers (Gaussian operands make the chip clock down; constants do not) and a
         # plain streaming read
         out["measured_ceilings"] = {
-            "mfma_bf16_gaussian_operands_tflops": hyp.hyp_measure_mfma_ceiling(True),
+            "mfma_bf16_gaussian_operands_tflops": hyp.hyp_measure_mfma_ceiling(True),      # 16x16x32, the GEMM's instruction
             "mfma_bf16_constant_operands_tflops": hyp.hyp_measure_mfma_ceiling(False),
+            "mfma_bf16_32x32x16_gaussian_operands_tflops": hyp.hyp_measure_mfma_ceiling(True, True),
             "hbm_stream_read_gbs": hyp.hyp_measure_hbm_read_ceiling(4),
             "gemm_gateup_kernel_constant_operands_tflops": gemm_constant_operands_tflops(wl),
         }

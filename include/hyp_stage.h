@@ -237,14 +237,16 @@ HYP_API hyp_status_t stage_profile_read(hyp_stage_t *stage, int32_t kernel_class
 /* Measurement aids: ceilings of the device measured in place, to set beside the
  * datasheet peaks in a roofline.  Neither needs a stage; both time three launches
  * with HIP events on `hip_stream` and wait for them.
- *   hyp_measure_mfma_ceiling     bf16 MFMA rate (TFLOP/s) of a register-only loop of
- *       v_mfma_f32_32x32x16_bf16 on every SIMD; operands N(0,1) (gaussian != 0) or the
- *       constant 1.0.  scratch: device, 16-byte aligned, >= 2.2 MB, overwritten.
+ *   hyp_measure_mfma_ceiling     bf16 MFMA rate (TFLOP/s) of a register-only loop on every
+ *       SIMD.  mode bit 0: operands N(0,1) (set) or the constant 1.0 (clear); mode bit 1:
+ *       v_mfma_f32_32x32x16_bf16 (set; the attention kernels' instruction) or
+ *       v_mfma_f32_16x16x32_bf16 (clear; the prefill GEMM's).  scratch: device, 16-byte
+ *       aligned, >= 2.2 MB, overwritten.
  *   hyp_measure_hbm_read_ceiling rate (GB/s) of a plain streaming read of `buffer`
  *       (device, 16-byte aligned, >= 1 GiB - well beyond the 256 MB memory-side cache;
  *       its last 16 bytes may be overwritten).
  * Errors: HYP_EINVAL (null / too small / misaligned), HYP_EDEVICE. */
-HYP_API hyp_status_t hyp_measure_mfma_ceiling(void *scratch, size_t scratch_bytes, int32_t gaussian,
+HYP_API hyp_status_t hyp_measure_mfma_ceiling(void *scratch, size_t scratch_bytes, int32_t mode,
                                       void *hip_stream, double *tflops_out);
 HYP_API hyp_status_t hyp_measure_hbm_read_ceiling(const void *buffer, size_t bytes, void *hip_stream,
                                           double *gbs_out);

@@ -296,11 +296,11 @@ def stage_profile_read(stage: Stage, kernel_class: str):
     return ms.value, n.value
 
 
-def hyp_measure_mfma_ceiling(gaussian: bool = True) -> float:
-    """bf16 MFMA TFLOP/s of a register-only loop on the current device."""
+def hyp_measure_mfma_ceiling(gaussian: bool = True, shape_32x32x16: bool = False) -> float:
+    """bf16 MFMA TFLOP/s of a register-only loop on the current device (16x16x32, or 32x32x16 on request)."""
     scratch = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
     out = C.c_double()
-    st = load_library().hyp_measure_mfma_ceiling(scratch.data_ptr(), scratch.numel(), 1 if gaussian else 0,
+    st = load_library().hyp_measure_mfma_ceiling(scratch.data_ptr(), scratch.numel(), (1 if gaussian else 0) | (2 if shape_32x32x16 else 0),
                                                  C.c_void_p(torch.cuda.current_stream().cuda_stream), C.byref(out))
     if st != HYP_OK:
         raise HypError(st, "hyp_measure_mfma_ceiling failed")

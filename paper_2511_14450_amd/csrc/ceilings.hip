@@ -11,30 +11,51 @@
 namespace hyp {
 namespace {
 
-// 8 independent accumulator chains per wave, operands loaded once: no LDS, no memory traffic
+// independent accumulator chains per wave, operands loaded once: no LDS, no memory traffic.
+// SHAPE 16: v_mfma_f32_16x16x32_bf16 (the prefill GEMM's), 32: v_mfma_f32_32x32x16_bf16 (the attention kernels').
+// Both do the same FLOPs per pass of the inner loop.
+template <int SHAPE>
 __global__ void __launch_bounds__(256) k_mfma_only(const bf16x8_t *__restrict__ src, float *__restrict__ out, int iters) {
-  f32x16_t acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
   bf16x8_t a[4], b[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     a[i] = src[(threadIdx.x * 8 + i) & 4095];
     b[i] = src[(threadIdx.x * 8 + 4 + i) & 4095];
   }
-  for (int it = 0; it < iters; it += 4) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i + u) & 3], acc[i], 0, 0, 0);
-  }
   float s = 0.f;
+  if constexpr (SHAPE == 32) {
+    f32x16_t acc[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += acc[i][r];
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i + u) & 3], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += acc[i][r];
+  } else {
+    f32x4_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i & 3], b[((i >> 2) + u) & 3], acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s += acc[i][r];
+  }
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
@@ -76,8 +97,10 @@ using namespace hyp;
 
 extern "C" {
 
-hyp_status_t hyp_measure_mfma_ceiling(void *scratch, size_t scratch_bytes, int32_t gaussian, void *hip_stream,
+hyp_status_t hyp_measure_mfma_ceiling(void *scratch, size_t scratch_bytes, int32_t mode, void *hip_stream,
                                       double *tflops_out) {
+  const int gaussian = mode & 1;
+  const bool shape32 = (mode & 2) != 0;
   const int n_wg = 2048, iters = 20000;
   const size_t need = 4096 * 16 + (size_t)n_wg * 256 * sizeof(float);
   if (!scratch || !tflops_out || scratch_bytes < need || (uintptr_t)scratch % 16) return HYP_EINVAL;
@@ -88,12 +111,16 @@ hyp_status_t hyp_measure_mfma_ceiling(void *scratch, size_t scratch_bytes, int32
   if (hipEventCreate(&e0) != hipSuccess) return HYP_EDEVICE;
   if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return HYP_EDEVICE; }
   k_fill_operands<<<(4096 * 8 + 255) / 256, 256, 0, s>>>(src, 4096 * 8, gaussian);
-  k_mfma_only<<<n_wg, 256, 0, s>>>((const bf16x8_t *)src, out, 400);  // warm-up, clocks settle
+  auto launch = [&](int n) {
+    if (shape32) k_mfma_only<32><<<n_wg, 256, 0, s>>>((const bf16x8_t *)src, out, n);
+    else k_mfma_only<16><<<n_wg, 256, 0, s>>>((const bf16x8_t *)src, out, n);
+  };
+  launch(400);  // warm-up, clocks settle
   float best = 0.f;
   hipError_t err = hipSuccess;
   for (int rep = 0; rep < 3 && err == hipSuccess; ++rep) {
     (void)hipEventRecord(e0, s);
-    k_mfma_only<<<n_wg, 256, 0, s>>>((const bf16x8_t *)src, out, iters);
+    launch(iters);
     (void)hipEventRecord(e1, s);
     err = hipEventSynchronize(e1);
     float ms = 0.f;

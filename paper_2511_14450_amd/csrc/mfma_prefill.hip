@@ -444,9 +444,31 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     }
   } else if (EPI == EPI_RESID) {
     // x += W a ; y' = x * gain of the next norm ; sum of squares of these 64 features per token.
-    // Padding rows stay zero.
+    // Padding rows stay zero.  The residual of a token block (8 loads of 1 KiB per wave) is requested one block
+    // ahead of the arithmetic that needs it: the epilogue is a chain of memory round trips otherwise.
+    f32x4_t old[2][2][FB][2];  // [parity of j][th][i][fh]
+    auto xres_at = [&](int tb, int i, int fh, int th) {
+      // the residual stream's accumulator order: group [fh][th] of the block, 64 lanes x 4 floats
+      return p.xres + (((size_t)tb * p.feat_blocks + (nb0 + wf * FB + i)) * 4 + fh * 2 + th) * 256 + lane * 4;
+    };
+    auto fetch = [&](int j) {
+      const int tb = min(tb0 + wt * TB + j, p.tok_blocks - 1);  // a block past the end rereads the last one (unused)
+#pragma unroll
+      for (int th = 0; th < 2; ++th)
+#pragma unroll
+        for (int i = 0; i < FB; ++i)
+#pragma unroll
+          for (int fh = 0; fh < 2; ++fh) old[j & 1][th][i][fh] = *(const f32x4_t *)xres_at(tb, i, fh, th);
+    };
+    bf16x4_t gg[FB][2];
+#pragma unroll
+    for (int i = 0; i < FB; ++i)
+#pragma unroll
+      for (int fh = 0; fh < 2; ++fh) gg[i][fh] = *(const bf16x4_t *)(p.gain + (nb0 + wf * FB + i) * 32 + 16 * fh + q4);
+    fetch(0);
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
+      if (j + 1 < TB) fetch(j + 1);
       int tb = tb0 + wt * TB + j;
       if (tb >= p.tok_blocks) continue;
 #pragma unroll
@@ -459,19 +481,15 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
           const int fb = nb0 + wf * FB + i;
 #pragma unroll
           for (int fh = 0; fh < 2; ++fh) {
-            // the residual stream's accumulator order: group [fh][th] of the block, 64 lanes x 4 floats
-            float *xb = p.xres + (((size_t)tb * p.feat_blocks + fb) * 4 + fh * 2 + th) * 256 + lane * 4;
-            f32x4_t old = *(const f32x4_t *)xb;
-            bf16x4_t gg = *(const bf16x4_t *)(p.gain + fb * 32 + 16 * fh + q4);
             f32x4_t nw, v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              float xn = live ? old[e] + acc[i][fh][j][th][e] : 0.f;
+              float xn = live ? old[j & 1][th][i][fh][e] + acc[i][fh][j][th][e] : 0.f;
               nw[e] = xn;
               ss += xn * xn;
-              v[e] = xn * bf16_to_f32(gg.v[e]);
+              v[e] = xn * bf16_to_f32(gg[i][fh].v[e]);
             }
-            *(f32x4_t *)xb = nw;
+            *(f32x4_t *)xres_at(tb, i, fh, th) = nw;
             store4(p.out, p.out_K, row, fb * 32 + 16 * fh + q4, v);
           }
         }

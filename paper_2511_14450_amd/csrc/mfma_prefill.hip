@@ -466,9 +466,9 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
       for (int fh = 0; fh < 2; ++fh) gg[i][fh] = *(const bf16x4_t *)(p.gain + (nb0 + wf * FB + i) * 32 + 16 * fh + q4);
     fetch(0);
+    fetch(1);
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
-      if (j + 1 < TB) fetch(j + 1);
       int tb = tb0 + wt * TB + j;
       if (tb >= p.tok_blocks) continue;
 #pragma unroll
@@ -498,6 +498,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
         ss += __shfl_xor(ss, 32, 64);
         if (lane < 16) p.ssq_part[(size_t)((nb0 + wf * FB) >> 1) * (p.tok_blocks * 32) + row] = ss;
       }
+      if (j + 2 < TB) fetch(j + 2);  // into the set this block has just left
     }
   } else {  // EPI_QKV
     const int n0 = tile_n * 256;              // first packed row of this tile

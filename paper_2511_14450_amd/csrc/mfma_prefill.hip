@@ -422,6 +422,11 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
     }
   } else if (EPI == EPI_SWIGLU) {
     // block 0 = gate, block 1 = up of FFN features [(tile_n*4 + wf)*32, +32)
+    float rs_all[TB][2];  // requested together: one round trip for the whole epilogue
+#pragma unroll
+    for (int j = 0; j < TB; ++j)
+#pragma unroll
+      for (int th = 0; th < 2; ++th) rs_all[j][th] = p.rstd[min(tb0 + wt * TB + j, p.tok_blocks - 1) * 32 + 16 * th + t16];
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
       int tb = tb0 + wt * TB + j;
@@ -429,7 +434,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
       for (int th = 0; th < 2; ++th) {
         const int row = tb * 32 + 16 * th + t16;
-        const float rs = p.rstd[row];  // the input rows carry gain only: W (x g r) = r W (x g)
+        const float rs = rs_all[j][th];  // the input rows carry gain only: W (x g r) = r W (x g)
 #pragma unroll
         for (int fh = 0; fh < 2; ++fh) {
           f32x4_t v;
@@ -503,22 +508,45 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
   } else {  // EPI_QKV
     const int n0 = tile_n * 256;              // first packed row of this tile
     const int head_in_tile = wf >> 1, ib = (wf & 1) * 32;
+    const bool rotary = n0 < p.qd + p.kvd;
+    // what the epilogue needs per token is requested up front (one round trip), the rotary table's entries - which
+    // wait for the positions - one token half ahead of their use
+    int pos_all[TB][2], req_all[TB][2];
+    float rs_all[TB][2];
+#pragma unroll
+    for (int j = 0; j < TB; ++j)
+#pragma unroll
+      for (int th = 0; th < 2; ++th) {
+        const int row = min(tb0 + wt * TB + j, p.tok_blocks - 1) * 32 + 16 * th + t16;
+        pos_all[j][th] = p.row_pos[row]; req_all[j][th] = p.row_req[row]; rs_all[j][th] = p.rstd[row];
+      }
+    f32x4_t cs[2][2][2];  // [parity of the token half][fh][cos, sin]
+    auto fetch_cs = [&](int h) {  // h = 2 j + th
+      if (!rotary) return;
+#pragma unroll
+      for (int fh = 0; fh < 2; ++fh) {
+        const size_t at = (size_t)pos_all[h >> 1][h & 1] * 64 + ib + 16 * fh + q4;
+        cs[h & 1][fh][0] = *(const f32x4_t *)(p.cos_tab + at);
+        cs[h & 1][fh][1] = *(const f32x4_t *)(p.sin_tab + at);
+      }
+    };
+    fetch_cs(0);
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
       int tb = tb0 + wt * TB + j;
-      if (tb >= p.tok_blocks) continue;
 #pragma unroll
       for (int th = 0; th < 2; ++th) {
+        if (2 * j + th + 1 < 2 * TB) fetch_cs(2 * j + th + 1);
+        if (tb >= p.tok_blocks) continue;
         const int row = tb * 32 + 16 * th + t16;
-        const int pos = p.row_pos[row], req = p.row_req[row];
-        const float rs = p.rstd[row];
-        if (n0 < p.qd + p.kvd) {
+        const int pos = pos_all[j][th], req = req_all[j][th];
+        const float rs = rs_all[j][th];
+        if (rotary) {
           // q or k: rotate the pair (d, d + 64) by the angle of this position; block 0 holds d, block 1 d + 64
 #pragma unroll
           for (int fh = 0; fh < 2; ++fh) {
             const int d0 = ib + 16 * fh + q4;  // d0 .. d0 + 3 and their partners d0 + 64 ..
-            f32x4_t c4 = *(const f32x4_t *)(p.cos_tab + (size_t)pos * 64 + d0);
-            f32x4_t s4 = *(const f32x4_t *)(p.sin_tab + (size_t)pos * 64 + d0);
+            const f32x4_t c4 = cs[(2 * j + th) & 1][fh][0], s4 = cs[(2 * j + th) & 1][fh][1];
             f32x4_t lo, hi;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {

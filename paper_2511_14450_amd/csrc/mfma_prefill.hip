@@ -194,7 +194,11 @@ struct AccLane {
 };
 // four consecutive features f0 .. f0+3 (f0 a multiple of 4) of internal row `row` into P(T', out_K): one 8-byte store
 __device__ __forceinline__ void store4(bf16_t *out, int out_K, int row, int f0, f32x4_t v) {
-  *(bf16x4_t *)(out + frag_offset(row, f0, out_K)) = pack4(v[0], v[1], v[2], v[3]);
+  // non-temporal, like all epilogue traffic: nothing of it is read again before it has left L2 anyway, and it
+  // should not push the operand panels out (O projection 5 % faster, gate/up 1.5 %)
+  typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned u32x2_t;
+  const bf16x4_t pk = pack4(v[0], v[1], v[2], v[3]);
+  __builtin_nontemporal_store(__builtin_bit_cast(u32x2_t, pk), (u32x2_t *)(out + frag_offset(row, f0, out_K)));
 }
 
 // CLS (a hyp_kernel_class_t) does not change the code: it gives each GEMM of a block a kernel name of its
@@ -463,7 +467,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
 #pragma unroll
         for (int i = 0; i < FB; ++i)
 #pragma unroll
-          for (int fh = 0; fh < 2; ++fh) old[j & 1][th][i][fh] = *(const f32x4_t *)xres_at(tb, i, fh, th);
+          for (int fh = 0; fh < 2; ++fh) old[j & 1][th][i][fh] = __builtin_nontemporal_load((const f32x4_t *)xres_at(tb, i, fh, th));
     };
     bf16x4_t gg[FB][2];
 #pragma unroll
@@ -494,7 +498,7 @@ __global__ void __launch_bounds__(WF * WT * 64) k_gemm(GemmParams p) {
               ss += xn * xn;
               v[e] = xn * bf16_to_f32(gg[i][fh].v[e]);
             }
-            *(f32x4_t *)xres_at(tb, i, fh, th) = nw;
+            __builtin_nontemporal_store(nw, (f32x4_t *)xres_at(tb, i, fh, th));
             store4(p.out, p.out_K, row, fb * 32 + 16 * fh + q4, v);
           }
         }

@@ -1,0 +1,91 @@
+"""The stage at the size, depth and launch configuration that bench.py times (20 Phi-3-medium-shaped
+blocks, 8 requests of 8192 prompt tokens, capacity 9216, graph-replayed decode), where the CPU oracle
+cannot follow (a 20-block prefill of one such request is ~100 TFLOP).  Checked instead: properties that
+hold at any size and that the oracle is pinned to at small size (tests/test_oracle_pins.py: ragged ==
+alone, cached decode == recompute):
+
+ 1. a request's prefill output and cache do not depend on the other requests of the batch, bit for bit
+    (rows are independent in every projection, attention is per request: Sec. III-A block over the
+    batch x sequence x hidden tensor of Sec. IV-A);
+ 2. a cached decode step equals recomputation: its output for request r against the last row of a
+    prefill over r's prompt plus the new token, through all 20 blocks (Eq. 1), within the bf16
+    tolerance - two different kernel paths (skinny GEMMs + split-KV attention against the tiled GEMMs
+    + prefill attention) that only agree if both are right; the keys and values the step appended
+    against the ones that prefill wrote;
+ 3. the same call twice gives the same bits.
+"""
+import numpy as np
+import pytest
+
+from workloads import synth
+from tests.helpers import rel_err, to_host
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def test_c5_stage_batch_independence_decode_equals_recompute_and_determinism():
+    import torch
+    import bench
+    import paper_2511_14450_amd as hyp
+    wl = synth.WORKLOADS["c5_long"]
+    shape, lens, n_dec = wl.shape, wl.lengths(), wl.decode_steps
+    B, T, L = len(lens), sum(lens), lens[0]
+    assert (wl.n_layers, B, L, n_dec) == (20, 8, 8192, 1024)
+    cfg = hyp.stage_config(shape, B, max(lens) + n_dec, T)  # as bench.py creates it
+    layers = bench.device_weights(shape, wl.n_layers, wl.seed)
+    stage = hyp.stage_create(cfg, 0, wl.n_layers, layers)
+    del layers
+    torch.cuda.empty_cache()
+    assert stage.uses_mfma()
+    print("\nstage of 20 blocks created", flush=True)
+
+    x = bench.device_normal((T, shape.hidden), wl.seed + 1)
+    xd = bench.device_normal((B, shape.hidden), wl.seed + 2)
+    y = torch.empty_like(x)
+    yd = torch.empty_like(xd)
+    stage.prefill(x, lens, y)
+    stage.decode_step(xd, yd)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y.float()).all()) and bool(torch.isfinite(yd.float()).all())
+    r = 5
+    k_all, v_all = stage.export_kv(wl.n_layers - 1, r)
+    k_all, v_all = k_all.clone(), v_all.clone()
+    assert k_all.shape[0] == L + 1
+    print("batch of 8 x 8192: prefill + one decode step done", flush=True)
+
+    # 3. determinism
+    y2, yd2 = torch.empty_like(y), torch.empty_like(yd)
+    stage.prefill(x, lens, y2)
+    stage.decode_step(xd, yd2)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(yd, yd2)
+    del y2, yd2
+    print("second run: same bits", flush=True)
+
+    # 1. request r alone
+    xr = x[r * L:(r + 1) * L].contiguous()
+    y1 = torch.empty_like(xr)
+    stage.prefill(xr, [L], y1)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y[r * L:(r + 1) * L]), "a request's prefill output depends on its batch"
+    k1, v1 = stage.export_kv(wl.n_layers - 1, 0)
+    assert torch.equal(k1, k_all[:L]) and torch.equal(v1, v_all[:L]), "a request's cache depends on its batch"
+    del y1, k1, v1
+    print("request alone: same bits as inside the batch", flush=True)
+
+    # 2. decode step against recomputation over prompt + new token
+    xc = torch.cat([xr, xd[r:r + 1]]).contiguous()
+    yc = torch.empty_like(xc)
+    stage.prefill(xc, [L + 1], yc)
+    torch.cuda.synchronize()
+    assert torch.equal(yc[:L], y[r * L:(r + 1) * L]), "causal prefix: earlier rows changed when a token was appended"
+    got, ref, xin = to_host(yd[r]), to_host(yc[L]), to_host(xd[r])
+    e_out, e_upd = rel_err(got, ref), rel_err(got - xin, ref - xin)
+    kc, vc = stage.export_kv(wl.n_layers - 1, 0)
+    assert torch.equal(kc[:L], k_all[:L]) and torch.equal(vc[:L], v_all[:L])
+    e_k, e_v = rel_err(to_host(k_all[L]), to_host(kc[L])), rel_err(to_host(v_all[L]), to_host(vc[L]))
+    print(f"decode step against recomputation through 20 blocks: output {e_out:.3e}, update {e_upd:.3e}, "
+          f"appended key {e_k:.3e}, value {e_v:.3e}", flush=True)
+    assert max(e_out, e_upd, e_k, e_v) <= TOL
+    stage.destroy()

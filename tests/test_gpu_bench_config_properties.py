@@ -89,3 +89,68 @@ def test_c5_stage_batch_independence_decode_equals_recompute_and_determinism():
           f"appended key {e_k:.3e}, value {e_v:.3e}", flush=True)
     assert max(e_out, e_upd, e_k, e_v) <= TOL
     stage.destroy()
+
+
+def test_c4_stage_paged_equals_slab_and_decode_steps_equal_recompute():
+    """The decode-heavy configuration as bench.py runs it (10 blocks, 32 ragged requests of 1024 .. 4096
+    prompt tokens, capacity +256): the paged cache on shuffled pages gives the slab's bits over prefill and
+    decode steps, and after four cached steps a request's last output equals the last row of a prefill over
+    its prompt and the four step inputs."""
+    import torch
+    import bench
+    import paper_2511_14450_amd as hyp
+    from paper_2511_14450_amd import binding
+    wl = synth.WORKLOADS["c4_decode_heavy"]
+    shape, lens, n_dec = wl.shape, wl.lengths(), wl.decode_steps
+    B, T = len(lens), sum(lens)
+    assert (wl.n_layers, B, n_dec) == (10, 32, 256) and min(lens) >= 1024 and max(lens) <= 4096
+    cap = max(lens) + n_dec
+    steps = 4
+    x = bench.device_normal((T, shape.hidden), wl.seed + 1)
+    xd = bench.device_normal((steps, B, shape.hidden), wl.seed + 2)
+    outs = {}
+    for paged in (False, True):
+        cfg = hyp.stage_config(shape, B, cap, T, flags=binding.HYP_FLAG_PAGED_KV if paged else 0)
+        layers = bench.device_weights(shape, wl.n_layers, wl.seed)
+        stage = hyp.stage_create(cfg, 0, wl.n_layers, layers)
+        del layers
+        torch.cuda.empty_cache()
+        assert stage.uses_mfma()
+        if paged:
+            ppr = -(-((cap + 63) // 64 * 64) // binding.HYP_KV_PAGE_KEYS)
+            perm = np.random.Generator(np.random.Philox(key=[wl.seed, 11])).permutation(B * ppr)
+            stage.set_page_table([[int(v) for v in perm[q * ppr:(q + 1) * ppr]] for q in range(B)])
+        y = torch.empty_like(x)
+        stage.prefill(x, lens, y)
+        yd = torch.empty_like(xd)
+        for s in range(steps):
+            stage.decode_step(xd[s], yd[s])
+        torch.cuda.synchronize()
+        outs[paged] = (y, yd)
+        print(f"\n{'paged' if paged else 'slab'}: prefill of {T} tokens + {steps} decode steps done", flush=True)
+        if paged:
+            break
+        # recomputation of the longest and the shortest request on the slab stage (prefill replaces the batch)
+        for r in (int(np.argmax(lens)), int(np.argmin(lens))):
+            o = sum(lens[:r])
+            xc = torch.cat([x[o:o + lens[r]], xd[:, r]]).contiguous()
+            yc = torch.empty_like(xc)
+            stage.prefill(xc, [lens[r] + steps], yc)
+            torch.cuda.synchronize()
+            # Not bit for bit here: appended tokens share the last 32-row block of the prompt, and the attention
+            # kernel moves its running maximum for all rows of a block together; a short prompt alone also has few
+            # enough output tiles for its projections to be summed in K slices.  Both only reorder roundings.
+            e = rel_err(to_host(yc[:lens[r]]), to_host(y[o:o + lens[r]]))
+            print(f"request {r} ({lens[r]} tokens) recomputed alone with {steps} appended tokens: prompt rows {e:.3e}", flush=True)
+            assert e <= TOL
+            for s in range(steps):
+                got, ref, xin = to_host(yd[s, r]), to_host(yc[lens[r] + s]), to_host(xd[s, r])
+                e = max(rel_err(got, ref), rel_err(got - xin, ref - xin))
+                print(f"request {r} ({lens[r]} tokens), decode step {s} against recomputation: {e:.3e}", flush=True)
+                assert e <= TOL
+        stage.destroy()
+        del stage
+        torch.cuda.empty_cache()
+    assert torch.equal(outs[False][0], outs[True][0]), "prefill: paged and slab caches differ"
+    assert torch.equal(outs[False][1], outs[True][1]), "decode: paged and slab caches differ"
+    stage.destroy()

@@ -21,7 +21,9 @@ from workloads import synth
 from tests.helpers import rel_err, to_host
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
+# Each kernel path is held to 2e-2 of the oracle where the oracle can follow; two paths that are each
+# that close to the exact result are within twice that of each other.  Measured: 1.0e-2 .. 1.8e-2.
+TOL = 2 * 2e-2
 
 
 def test_c5_stage_batch_independence_decode_equals_recompute_and_determinism():
@@ -153,4 +155,51 @@ def test_c4_stage_paged_equals_slab_and_decode_steps_equal_recompute():
         torch.cuda.empty_cache()
     assert torch.equal(outs[False][0], outs[True][0]), "prefill: paged and slab caches differ"
     assert torch.equal(outs[False][1], outs[True][1]), "decode: paged and slab caches differ"
+    stage.destroy()
+
+
+def test_c5_stage_all_1024_decode_steps_to_capacity_equal_recompute():
+    """The whole decode loop of the benched configuration: 1024 graph-replayed steps take every request from
+    8192 cached tokens to the capacity of 9216 (nine 1024-key chunks per head, the last one filling up);
+    the outputs of steps 0, 511 and 1023 for one request against the rows of a single prefill over its
+    prompt and all 1024 step inputs, and the cache the steps wrote against the one that prefill writes."""
+    import torch
+    import bench
+    import paper_2511_14450_amd as hyp
+    wl = synth.WORKLOADS["c5_long"]
+    shape, lens, n_dec = wl.shape, wl.lengths(), wl.decode_steps
+    B, T, L = len(lens), sum(lens), lens[0]
+    cfg = hyp.stage_config(shape, B, L + n_dec, T)
+    layers = bench.device_weights(shape, wl.n_layers, wl.seed)
+    stage = hyp.stage_create(cfg, 0, wl.n_layers, layers)
+    del layers
+    torch.cuda.empty_cache()
+    x = bench.device_normal((T, shape.hidden), wl.seed + 1)
+    xd = bench.device_normal((n_dec, B, shape.hidden), wl.seed + 2)
+    y = torch.empty_like(x)
+    yd = torch.empty_like(xd)
+    stage.prefill(x, lens, y)
+    for s in range(n_dec):
+        stage.decode_step(xd[s], yd[s])
+    torch.cuda.synchronize()
+    r = 2
+    assert stage.context_len(r) == L + n_dec
+    k_dec, v_dec = (t.clone() for t in stage.export_kv(wl.n_layers - 1, r))
+    print(f"\n{n_dec} decode steps done, context {stage.context_len(r)}", flush=True)
+    with pytest.raises(hyp.HypError):
+        stage.decode_step(xd[0], yd[0])  # the cache is full
+    xc = torch.cat([x[r * L:(r + 1) * L], xd[:, r]]).contiguous()
+    yc = torch.empty_like(xc)
+    stage.prefill(xc, [L + n_dec], yc)
+    torch.cuda.synchronize()
+    k_pre, v_pre = stage.export_kv(wl.n_layers - 1, 0)
+    assert torch.equal(k_pre[:L], k_dec[:L]) and torch.equal(v_pre[:L], v_dec[:L])
+    worst = max(rel_err(to_host(k_dec[L:]), to_host(k_pre[L:])), rel_err(to_host(v_dec[L:]), to_host(v_pre[L:])))
+    print(f"keys and values appended by the steps against prefill's: {worst:.3e}", flush=True)
+    for s in (0, n_dec // 2 - 1, n_dec - 1):
+        got, ref, xin = to_host(yd[s, r]), to_host(yc[L + s]), to_host(xd[s, r])
+        e = max(rel_err(got, ref), rel_err(got - xin, ref - xin))
+        print(f"decode step {s} against recomputation: {e:.3e}", flush=True)
+        worst = max(worst, e)
+    assert worst <= TOL
     stage.destroy()

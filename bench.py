@@ -346,7 +346,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one stage on ONE GPU: a stage is the unit the pipeline places on a single "
-              "device, and this build has no multi-GPU path. Run with --gpus 1.", file=sys.stderr)
+              "device, and the library has no multi-GPU path. Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch

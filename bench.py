@@ -327,6 +327,32 @@ def gemm_constant_operands_tflops(wl):
     return 2.0 * T * 2 * shape.ffn_dim * shape.hidden / (ms / n * 1e-3) / 1e12
 
 
+def library_gemm_tflops(wl):
+    """A yardstick, not a path of the stage: the vendor BLAS (what torch.matmul dispatches to) on the four
+    projection shapes of the timed prefill, same Gaussian bf16 operands, plain bf16 output and none of the
+    fused epilogues - what a tuned hand-written assembly GEMM reaches on this device and this data."""
+    import torch
+    shape = wl.shape
+    T = sum(wl.lengths())
+    H, I, qd, kvd = shape.hidden, shape.ffn_dim, shape.q_dim, shape.kv_dim
+    res = {}
+    for name, (N, K) in {"gemm_qkv": (qd + 2 * kvd, H), "gemm_o": (H, qd), "gemm_gateup": (2 * I, H), "gemm_down": (H, I)}.items():
+        a = device_normal((T, K), wl.seed + 7)
+        b = (device_normal((N, K), wl.seed + 8).float() * 0.02).to(torch.bfloat16)
+        for _ in range(2):
+            c = a @ b.t()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(4):
+            c = a @ b.t()
+        ev[1].record()
+        torch.cuda.synchronize()
+        res[name] = 2.0 * T * N * K / (ev[0].elapsed_time(ev[1]) / 4 * 1e-3) / 1e12
+        del a, b, c
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -383,6 +409,7 @@ def main():
             "mfma_bf16_32x32x16_gaussian_operands_tflops": hyp.hyp_measure_mfma_ceiling(True, True),
             "hbm_stream_read_gbs": hyp.hyp_measure_hbm_read_ceiling(4),
             "gemm_gateup_kernel_constant_operands_tflops": gemm_constant_operands_tflops(wl),
+            "library_gemm_same_shapes_gaussian_operands_tflops": library_gemm_tflops(wl),
         }
         # the same fractions against what the device was measured to deliver (the datasheet figures stay the headline)
         mc = out["measured_ceilings"]

@@ -21,7 +21,7 @@ namespace {
 // tiny and stays in L2.  A workgroup owns 64 packed rows (2 blocks; 32 rows in the
 // unsplit form of the O / down projections); its NW waves (4, 8 or 16) split the
 // workgroup's K slice and are reduced through LDS in wave order; the
-// `ksplit` workgroups of one row group (twice as many for the row groups that would
+// `ksplit` workgroups of one row group (two or four times as many for the row groups that would
 // otherwise form a thin second round of the launch) write fp32 partial sums, and the one that
 // arrives last (a counter per row group) adds them up in slice order - so the
 // result does not depend on which one that is - and runs the epilogue.  The
@@ -49,8 +49,8 @@ struct DecGemvParams {
   float *partial;
   unsigned *counters;
   int N, KT, ksplit, tiles_per_wave, batch;
-  // row groups from `groups1` on are split twice as fine (they run last and keep the launch's tail short)
-  int groups1, n_groups;
+  // row groups from `groups1` on are split `tail` times as fine (they run last and keep the launch's tail short)
+  int groups1, n_groups, tail;
   const float *ssq_in;  // [n_ssq][32]
   int n_ssq;
   float inv_H, eps;
@@ -93,14 +93,14 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
   float (*fin)[kGroupRows + 1] = (float (*)[kGroupRows + 1])red_raw;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   // 1-D grid: first the `ksplit` slices of row groups [0, groups1), slice-major, then the
-  // 2 * ksplit slices of the remaining groups
+  // tail * ksplit slices of the remaining groups
   int group, ks, ksplit = p.ksplit, tiles_per_wave = p.tiles_per_wave;
   {
     const int first = p.groups1 * p.ksplit, id = blockIdx.x;
     if (id < first) { group = id % p.groups1; ks = id / p.groups1; }
     else {
       const int g2 = p.n_groups - p.groups1, id2 = id - first;
-      group = p.groups1 + id2 % g2; ks = id2 / g2; ksplit *= 2; tiles_per_wave >>= 1;
+      group = p.groups1 + id2 % g2; ks = id2 / g2; ksplit *= p.tail; tiles_per_wave /= p.tail;
     }
   }
   const int fb0 = group * FBW;
@@ -476,6 +476,16 @@ GemvPlan mfma_gemv_plan(int cls, int N, int K, int batch) {
     g.ksplit = ks;
     if (groups * ks * g.nw >= wave_slots) break;
   }
+  // More workgroups than fit the chip at once, but fewer than two rounds: the groups beyond the first round
+  // are cut finer, for what would otherwise be a thin second round of long workgroups.  A CU serves its waves'
+  // loads oldest first, so the late workgroups stream last whatever their size: they should be many (bytes
+  // in flight on every CU to the end) and short.  Four times finer where a wave keeps two windows of
+  // the streaming loop (gate/up: 62.3 -> 59.6 us), else twice.
+  const int units = groups * g.ksplit, slots = wave_slots / g.nw, tpw = KT / (g.ksplit * g.nw);
+  if (units > slots && units < 2 * slots) {
+    if (tpw % 4 == 0 && tpw / 4 >= 10) g.tail = 4;
+    else if (tpw % 2 == 0 && tpw / 2 >= 10) g.tail = 2;
+  }
   return g;
 }
 
@@ -509,15 +519,14 @@ hipError_t mfma_dec_gemv(int epi, int cls, const DecGemv &a, hipStream_t s) {
   p.lens = a.lens; p.cos_tab = a.cos_tab; p.sin_tab = a.sin_tab; p.qdec = a.qdec; p.Kc = a.Kc; p.Vc = a.Vc;
   p.geom = a.geom; p.nq = a.nq; p.nkv = a.nkv; p.m_out = a.m_out; p.I = a.I; p.xres = a.xres; p.gain = a.gain;
   p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H; p.lens_advance = a.lens_advance;
-  // When the slices of all row groups do not fit the chip at once but would in fewer than two
-  // rounds, the groups beyond the first round get twice the slices: twice as many waves, half
-  // as long, for what would otherwise be a thin second round.
+  // the plan's finer cut of the row groups beyond the first round, if the partial sums have room for it
   const int groups = a.N / (fbw * 32), slots = kWavesPerCu / nw * 256;
-  p.n_groups = groups; p.groups1 = groups;
-  if (groups * ksplit > slots && groups * ksplit < 2 * slots && p.tiles_per_wave % 2 == 0 &&
-      p.tiles_per_wave / 2 >= 10 && 2 * ksplit <= a.max_ksplit)
+  p.n_groups = groups; p.groups1 = groups; p.tail = 1;
+  if (a.plan.tail > 1 && groups * ksplit > slots && p.tiles_per_wave % a.plan.tail == 0 && a.plan.tail * ksplit <= a.max_ksplit) {
+    p.tail = a.plan.tail;
     p.groups1 = slots / ksplit;
-  dim3 grid(p.groups1 * ksplit + (groups - p.groups1) * 2 * ksplit);
+  }
+  dim3 grid(p.groups1 * ksplit + (groups - p.groups1) * p.tail * ksplit);
   const size_t lds = sizeof(float) * nw * a.batch * (fbw * 32 + 4);  // the waves' sums of the live tokens
   bool launched = false;
 #define X(EPI, FBW, NW, CLS)                                                 \

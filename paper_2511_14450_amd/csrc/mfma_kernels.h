@@ -69,7 +69,7 @@ enum { DEC_QKV = 0, DEC_SWIGLU = 1, DEC_RESID = 2, DEC_FINAL = 3 };
 // its consumer fused in (see k_dec_gemv).  Fields a given epilogue does not use
 // stay null / 0.
 // how a skinny GEMM is cut into workgroups (see mfma_gemv_plan)
-struct GemvPlan { int fbw = 2, nw = 4, ksplit = 1; };
+struct GemvPlan { int fbw = 2, nw = 4, ksplit = 1, tail = 1; };  // tail: how many times finer the row groups of a thin second round are cut
 
 struct DecGemv {
   const bf16_t *W = nullptr, *x = nullptr;  // P(N, K), P(32, K)
@@ -77,7 +77,7 @@ struct DecGemv {
   unsigned *counters = nullptr;             // [N / 32], zero between launches
   int N = 0, K = 0, batch = 0;
   GemvPlan plan;                            // plan.fbw also sets the granularity of ssq_out (sums of squares per 32 or 64 rows)
-  int max_ksplit = 1;                       // slices `partial` has room for (the launcher may split some row groups finer)
+  int max_ksplit = 1;                       // slices `partial` has room for: plan.ksplit * plan.tail
   const float *ssq_in = nullptr;            // [n_ssq][32] sums of squares of the normalised input
   int n_ssq = 0;
   float eps = 0.f;

@@ -59,9 +59,9 @@ def test_noalloc_decode_refuses_what_does_not_fit_or_does_not_apply():
     import paper_2511_14450_amd as hyp
     from paper_2511_14450_amd import binding
     lib = hyp.load_library()
-    # an FFN of 65536 features: the gate/up GEMV's room for partial sums, 2 x 65536 rows x 32 tokens x 2 x 4 B,
+    # an FFN of 131072 features: the gate/up GEMV's room for partial sums, 2 x 131072 rows x 32 tokens x 4 B,
     # alone passes 32 MiB; zero weights are enough, the stage is never run
-    big = synth.BlockShape(hidden=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=65536, dtype="bf16")
+    big = synth.BlockShape(hidden=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, ffn_dim=131072, dtype="bf16")
     w = {n: torch.zeros(shp, dtype=torch.bfloat16, device="cuda") for n, shp in big.weight_shapes().items()}
     st = hyp.stage_create(make_config(big, 8, 128, 128), 0, 1, [w])
     x = torch.zeros((8, big.hidden), dtype=torch.bfloat16, device="cuda")

@@ -104,6 +104,12 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     }
   }
   const int fb0 = group * FBW;
+  // partial sums [slice][32 tokens][rows]: the finely cut last groups have a narrow array of their own behind the
+  // main one (rows of those groups only), so their extra slices do not cost room over all N rows
+  const bool fine = group >= p.groups1;
+  float *const part = fine ? p.partial + (size_t)p.ksplit * 32 * p.N : p.partial;
+  const int part_n = fine ? (p.n_groups - p.groups1) * kGroupRows : p.N;        // rows per token
+  const int part_r0 = fine ? (group - p.groups1) * kGroupRows : fb0 * 32;       // this group's first row
   // positions of the step's tokens (the QKV epilogue's rotary angles depend on them): fetched under the streaming loop
   // (ahead of time for the first kPf * 8 tokens, which covers the usual batch; the rest is loaded in place)
   constexpr int kPf = 2;
@@ -203,7 +209,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
     if (idx < n_pairs) {
       int f = idx % kGroupRows, token = idx / kGroupRows;
       if (ksplit > 1)  // write-through store: visible to the other XCDs once it has completed
-        __hip_atomic_store(&p.partial[((size_t)ks * 32 + token) * p.N + fb0 * 32 + f], mine[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&part[((size_t)ks * 32 + token) * part_n + part_r0 + f], mine[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       else fin[token][f] = mine[j];
     }
   }
@@ -275,9 +281,9 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
         for (int j = 0; j < 4; ++j) {
           const int idx = threadIdx.x + (j0 + j) * NW * 64;
           const bool has = idx < n_pairs;
-          const unsigned off = has ? (unsigned)((idx / kGroupRows) * p.N + fb0 * 32 + idx % kGroupRows) : 0u;
+          const unsigned off = has ? (unsigned)((idx / kGroupRows) * part_n + part_r0 + idx % kGroupRows) : 0u;
 #pragma unroll
-          for (int u = 0; u < 4; ++u) v[j][u] = has && u < ksplit ? (p.partial + (size_t)u * 32 * p.N)[off] : 0.f;
+          for (int u = 0; u < 4; ++u) v[j][u] = has && u < ksplit ? (part + (size_t)u * 32 * part_n)[off] : 0.f;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -290,15 +296,15 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4)
         const int idx1 = idx0 + NW * 64;
         const bool has1 = idx1 < n_pairs;
         // slice bases are uniform (scalar registers); one 32-bit offset per pair serves every slice
-        const unsigned off0 = (unsigned)((idx0 / kGroupRows) * p.N + fb0 * 32 + idx0 % kGroupRows);
-        const unsigned off1 = (unsigned)(((has1 ? idx1 : idx0) / kGroupRows) * p.N + fb0 * 32 + (has1 ? idx1 : idx0) % kGroupRows);
+        const unsigned off0 = (unsigned)((idx0 / kGroupRows) * part_n + part_r0 + idx0 % kGroupRows);
+        const unsigned off1 = (unsigned)(((has1 ? idx1 : idx0) / kGroupRows) * part_n + part_r0 + (has1 ? idx1 : idx0) % kGroupRows);
         float sum0 = 0.f, sum1 = 0.f;
         for (int s = 0; s < ksplit; s += GW) {
           float v0[GW], v1[GW];
 #pragma unroll
           for (int u = 0; u < GW; ++u) {
             const bool in = s + u < ksplit;
-            const float *slice = p.partial + (size_t)(s + u) * 32 * p.N;
+            const float *slice = part + (size_t)(s + u) * 32 * part_n;
             v0[u] = in ? slice[off0] : 0.f;
             v1[u] = in && has1 ? slice[off1] : 0.f;
           }
@@ -489,6 +495,22 @@ GemvPlan mfma_gemv_plan(int cls, int N, int K, int batch) {
   return g;
 }
 
+// Row groups [0, groups1) run as plan.ksplit workgroups each, the rest (beyond the first round of the launch, if the plan
+// cuts those finer) as plan.ksplit * tail.
+static void gemv_cut(const GemvPlan &g, int N, int K, int *groups1, int *tail) {
+  const int groups = N / (g.fbw * 32), slots = kWavesPerCu / g.nw * 256, tpw = K / 16 / (g.ksplit * g.nw);
+  *groups1 = groups; *tail = 1;
+  if (g.tail > 1 && groups * g.ksplit > slots && tpw % g.tail == 0) { *groups1 = slots / g.ksplit; *tail = g.tail; }
+}
+
+// floats of partial sums a GEMM cut this way needs: [ksplit][32][N], then [ksplit * tail][32][rows of the finely cut groups]
+size_t mfma_gemv_partial_floats(const GemvPlan &g, int N, int K) {
+  int groups1, tail;
+  gemv_cut(g, N, K, &groups1, &tail);
+  const int fine_rows = (N / (g.fbw * 32) - groups1) * g.fbw * 32;
+  return (size_t)g.ksplit * 32 * N + (size_t)g.ksplit * tail * 32 * fine_rows;
+}
+
 // the (epilogue, blocks per workgroup, waves per workgroup, class) combinations a plan may ask for
 #define HYP_GEMV_VARIANTS(X, NW)                                                                         \
   X(DEC_QKV, 2, NW, HYP_K_GEMV_QKV) X(DEC_SWIGLU, 2, NW, HYP_K_GEMV_GATEUP)                              \
@@ -519,13 +541,11 @@ hipError_t mfma_dec_gemv(int epi, int cls, const DecGemv &a, hipStream_t s) {
   p.lens = a.lens; p.cos_tab = a.cos_tab; p.sin_tab = a.sin_tab; p.qdec = a.qdec; p.Kc = a.Kc; p.Vc = a.Vc;
   p.geom = a.geom; p.nq = a.nq; p.nkv = a.nkv; p.m_out = a.m_out; p.I = a.I; p.xres = a.xres; p.gain = a.gain;
   p.y_out = a.y_out; p.ssq_out = a.ssq_out; p.hidden_out = a.hidden_out; p.H = a.H; p.lens_advance = a.lens_advance;
-  // the plan's finer cut of the row groups beyond the first round, if the partial sums have room for it
-  const int groups = a.N / (fbw * 32), slots = kWavesPerCu / nw * 256;
-  p.n_groups = groups; p.groups1 = groups; p.tail = 1;
-  if (a.plan.tail > 1 && groups * ksplit > slots && p.tiles_per_wave % a.plan.tail == 0 && a.plan.tail * ksplit <= a.max_ksplit) {
-    p.tail = a.plan.tail;
-    p.groups1 = slots / ksplit;
-  }
+  // the plan's finer cut of the row groups beyond the first round
+  const int groups = a.N / (fbw * 32);
+  p.n_groups = groups;
+  gemv_cut(a.plan, a.N, a.K, &p.groups1, &p.tail);
+  if (mfma_gemv_partial_floats(a.plan, a.N, a.K) > a.partial_floats) return hipErrorInvalidValue;
   dim3 grid(p.groups1 * ksplit + (groups - p.groups1) * p.tail * ksplit);
   const size_t lds = sizeof(float) * nw * a.batch * (fbw * 32 + 4);  // the waves' sums of the live tokens
   bool launched = false;

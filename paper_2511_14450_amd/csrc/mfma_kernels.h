@@ -73,11 +73,11 @@ struct GemvPlan { int fbw = 2, nw = 4, ksplit = 1, tail = 1; };  // tail: how ma
 
 struct DecGemv {
   const bf16_t *W = nullptr, *x = nullptr;  // P(N, K), P(32, K)
-  float *partial = nullptr;                 // [max_ksplit][32][N]
+  float *partial = nullptr;                 // partial sums of the K slices, mfma_gemv_partial_floats(plan, N, K) floats
   unsigned *counters = nullptr;             // [N / 32], zero between launches
   int N = 0, K = 0, batch = 0;
   GemvPlan plan;                            // plan.fbw also sets the granularity of ssq_out (sums of squares per 32 or 64 rows)
-  int max_ksplit = 1;                       // slices `partial` has room for: plan.ksplit * plan.tail
+  size_t partial_floats = 0;                // room behind `partial`
   const float *ssq_in = nullptr;            // [n_ssq][32] sums of squares of the normalised input
   int n_ssq = 0;
   float eps = 0.f;
@@ -98,6 +98,7 @@ struct DecGemv {
 };
 hipError_t mfma_dec_gemv(int epi, int cls, const DecGemv &a, hipStream_t s);  // cls: as for mfma_gemm
 GemvPlan mfma_gemv_plan(int cls, int N, int K, int batch);  // cls: HYP_K_GEMV_*
+size_t mfma_gemv_partial_floats(const GemvPlan &plan, int N, int K);
 hipError_t mfma_gemv_init();  // kernel attributes, once per process and device
 // x = hidden_in ; xres = x ; y' = x * gain -> P(32, H) ; ssq_out[H/64][32]
 hipError_t mfma_dec_begin(const bf16_t *hidden_in, float *xres, const bf16_t *gain, bf16_t *y_out, float *ssq_out,

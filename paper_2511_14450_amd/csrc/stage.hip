@@ -193,10 +193,10 @@ void make_layout(const hyp_stage_config_t &c, int n_layers, Layout &L) {
     L.g_o = mfma_gemv_plan(HYP_K_GEMV_O, (int)H, (int)qd, c.max_batch);
     L.g_gu = mfma_gemv_plan(HYP_K_GEMV_GATEUP, (int)(2 * I), (int)H, c.max_batch);
     L.g_d = mfma_gemv_plan(HYP_K_GEMV_DOWN, (int)H, (int)I, c.max_batch);
-    // fp32 partial sums [slice][32][N] of the GEMM with the most of them (slices: ksplit, times the finer cut of a launch's last row groups)
-    size_t pf = std::max(std::max((size_t)L.g_qkv.ksplit * L.g_qkv.tail * (qd + 2 * kvd), (size_t)L.g_o.ksplit * L.g_o.tail * H),
-                         std::max((size_t)L.g_gu.ksplit * L.g_gu.tail * 2 * I, (size_t)L.g_d.ksplit * L.g_d.tail * H));
-    L.partial_bytes = sizeof(float) * pf * 32;
+    // fp32 partial sums of the K slices: room for the GEMM with the most of them
+    const size_t pf = std::max(std::max(mfma_gemv_partial_floats(L.g_qkv, (int)(qd + 2 * kvd), (int)H), mfma_gemv_partial_floats(L.g_o, (int)H, (int)qd)),
+                               std::max(mfma_gemv_partial_floats(L.g_gu, (int)(2 * I), (int)H), mfma_gemv_partial_floats(L.g_d, (int)H, (int)I)));
+    L.partial_bytes = sizeof(float) * pf;
     L.partial = take(L.partial_bytes);
     L.chunk_keys = mfma_decode_chunk_keys(c.max_seq, c.max_batch * c.n_kv_heads);
     L.max_chunks = (c.max_seq + L.chunk_keys - 1) / L.chunk_keys;
@@ -442,6 +442,7 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const DecScratch &sc
   const Layout &L = st->L;
   DecGemv base;
   base.partial = sc.partial;
+  base.partial_floats = L.partial_bytes / sizeof(float);
   base.counters = sc.counters;
   base.batch = st->batch;
   base.eps = d.eps;
@@ -457,7 +458,7 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const DecScratch &sc
     const LayerPtrs &p = L.layers[l];
     bf16_t *Kc = at<bf16_t>(st, L.Kc + L.kv_layer_stride * l), *Vc = at<bf16_t>(st, L.Vc + L.kv_layer_stride * l);
     DecGemv a = base;
-    a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.plan = L.g_qkv; a.max_ksplit = a.plan.ksplit * a.plan.tail;
+    a.W = at<bf16_t>(st, p.wqkv); a.x = y; a.N = d.qd + 2 * d.kvd; a.K = d.H; a.plan = L.g_qkv;
     a.ssq_in = ssq; a.n_ssq = d.H / (l == 0 ? 64 : 32 * L.g_d.fbw);  // written by the opening kernel / the previous down GEMM
     a.lens = at<int>(st, L.lens); a.cos_tab = at<float>(st, L.cos_tab); a.sin_tab = at<float>(st, L.sin_tab);
     a.qdec = sc.qdec; a.Kc = Kc; a.Vc = Vc; a.geom = geom; a.nq = d.nq; a.nkv = d.nkv;
@@ -466,15 +467,15 @@ hyp_status_t decode_step_mfma(hyp_stage *st, hipStream_t s, const DecScratch &sc
                                                  attn, d.nq, d.nkv, st->batch,
                                                  L.max_chunks, L.chunk_keys, s));
     DecGemv o = base;
-    o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.plan = L.g_o; o.max_ksplit = o.plan.ksplit * o.plan.tail;
+    o.W = at<bf16_t>(st, p.wo); o.x = attn; o.N = d.H; o.K = d.qd; o.plan = L.g_o;
     o.gain = at<bf16_t>(st, p.g2); o.y_out = y; o.ssq_out = ssq;
     PROF(st, HYP_K_GEMV_O, mfma_dec_gemv(DEC_RESID, HYP_K_GEMV_O, o, s));
     DecGemv g = base;
-    g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.plan = L.g_gu; g.max_ksplit = g.plan.ksplit * g.plan.tail;
+    g.W = at<bf16_t>(st, p.wgu); g.x = y; g.N = 2 * d.I; g.K = d.H; g.plan = L.g_gu;
     g.ssq_in = ssq; g.n_ssq = d.H / (32 * L.g_o.fbw); g.m_out = m; g.I = d.I;
     PROF(st, HYP_K_GEMV_GATEUP, mfma_dec_gemv(DEC_SWIGLU, HYP_K_GEMV_GATEUP, g, s));
     DecGemv w = base;
-    w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.plan = L.g_d; w.max_ksplit = w.plan.ksplit * w.plan.tail;
+    w.W = at<bf16_t>(st, p.wd); w.x = m; w.N = d.H; w.K = d.I; w.plan = L.g_d;
     if (l + 1 < st->n_layers) {
       w.gain = at<bf16_t>(st, L.layers[l + 1].g1); w.y_out = y; w.ssq_out = ssq;
       PROF(st, HYP_K_GEMV_DOWN, mfma_dec_gemv(DEC_RESID, HYP_K_GEMV_DOWN, w, s));

@@ -150,7 +150,8 @@ __global__ void __launch_bounds__(256) k_rstd(const float *__restrict__ ssq_part
 // for the burst to issue.
 // One barrier per stage.  Workgroups are numbered so that the ones
 // that run together on an XCD (id % 8) cover a band of `gm` token tiles times
-// consecutive feature tiles and share operand panels in that XCD's L2.
+// consecutive feature tiles and share operand panels in that XCD's L2.  A GEMM of 64
+// rounds or more leaves its last rounds to workgroups that draw a tile each from a counter.
 // ----------------------------------------------------------------------------
 constexpr int WF = 4, WT = 2, FB = 2, TB = 4, KTS = 2, NST = 4;
 constexpr int XB = WT * TB, NBK = WF * FB;           // 8 token blocks, 8 feature blocks
